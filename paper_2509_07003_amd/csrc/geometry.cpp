@@ -1,0 +1,264 @@
+#include "geometry.hpp"
+
+#include <algorithm>
+
+namespace vesrng {
+
+namespace {
+
+constexpr int kMaxDims = 8;
+constexpr uint64_t kMaxNumel = 1ull << 62;
+
+// The global indices a rank holds along ONE tensor dimension, kept as a
+// row-major box: index(t_0, .., t_{m-1}) = origin + sum t_k * step_k, local
+// order = row-major over (t_0 .. t_{m-1}).  A fresh dimension is one axis of
+// step 1; InterleavedShard adds an axis.
+struct Sub {
+  int64_t extent;
+  int64_t step;
+};
+struct DimBox {
+  std::vector<Sub> subs;  // outermost first
+  int64_t origin = 0;
+  int64_t length() const {
+    int64_t n = 1;
+    for (const Sub& s : subs) n *= s.extent;
+    return n;
+  }
+};
+
+// Keeps entries [start, start + len) of the row-major list of subs[from..].
+// Possible in closed form when the range is whole rows of the leading axis or
+// lies inside one of its rows.
+bool slice(DimBox& box, size_t from, int64_t start, int64_t len) {
+  if (len == 0) {
+    box.subs.assign(1, Sub{0, 1});
+    return true;
+  }
+  if (from + 1 == box.subs.size()) {
+    box.origin += start * box.subs[from].step;
+    box.subs[from].extent = len;
+    return true;
+  }
+  int64_t inner = 1;
+  for (size_t k = from + 1; k < box.subs.size(); ++k) inner *= box.subs[k].extent;
+  if (start % inner == 0 && len % inner == 0) {
+    box.origin += (start / inner) * box.subs[from].step;
+    box.subs[from].extent = len / inner;
+    return true;
+  }
+  if (start / inner == (start + len - 1) / inner) {
+    box.origin += (start / inner) * box.subs[from].step;
+    box.subs[from].extent = 1;
+    return slice(box, from + 1, start % inner, len);
+  }
+  return false;
+}
+
+// Start and length of chunk `which` when `n` entries are cut into `parts`
+// consecutive chunks of ceil(n / parts).
+void chunk_range(int64_t n, int64_t parts, int64_t which, int64_t* start, int64_t* len) {
+  const int64_t q = (n + parts - 1) / parts;
+  const int64_t b = std::min(n, q * which);
+  const int64_t e = std::min(n, q * (which + 1));
+  *start = b;
+  *len = e - b;
+}
+
+vesrng_status apply_shard(DimBox& box, int64_t parts, int64_t which) {
+  int64_t start, len;
+  chunk_range(box.length(), parts, which, &start, &len);
+  return slice(box, 0, start, len) ? VESRNG_OK : VESRNG_ERR_UNSUPPORTED;
+}
+
+vesrng_status apply_interleaved(DimBox& box, int64_t groups, int64_t parts, int64_t which) {
+  const int64_t n = box.length();
+  if (groups < 1 || n % groups != 0) return VESRNG_ERR_BAD_PLACEMENT;
+  if (n == 0) return VESRNG_OK;
+  // Make the leading axes enumerate exactly `groups` groups.
+  int64_t remaining = groups;
+  size_t k = 0;
+  while (remaining > 1) {
+    if (k >= box.subs.size()) return VESRNG_ERR_UNSUPPORTED;
+    const int64_t e = box.subs[k].extent;
+    if (e % remaining == 0) {
+      const int64_t per = e / remaining;
+      const int64_t step = box.subs[k].step;
+      box.subs[k] = Sub{remaining, step * per};
+      box.subs.insert(box.subs.begin() + static_cast<long>(k) + 1, Sub{per, step});
+      remaining = 1;
+      ++k;
+    } else if (remaining % e == 0) {
+      remaining /= e;
+      ++k;
+    } else {
+      return VESRNG_ERR_UNSUPPORTED;
+    }
+  }
+  if (k == box.subs.size()) box.subs.push_back(Sub{1, 1});  // groups of one entry
+  int64_t start, len;
+  chunk_range(n / groups, parts, which, &start, &len);
+  if (len == 0) {
+    box.subs.assign(1, Sub{0, 1});
+    return VESRNG_OK;
+  }
+  return slice(box, k, start, len) ? VESRNG_OK : VESRNG_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
+  if (!s || !g) return VESRNG_ERR_NULL;
+  if (s->ndim < 0 || s->ndim > kMaxDims) return VESRNG_ERR_BAD_SHAPE;
+  if (s->mesh_ndim < 0 || s->mesh_ndim > kMaxDims) return VESRNG_ERR_BAD_MESH;
+  if (s->ndim > 0 && !s->global_shape) return VESRNG_ERR_NULL;
+  if (s->mesh_ndim > 0 && (!s->mesh_shape || !s->placements || !s->mesh_coord)) return VESRNG_ERR_NULL;
+
+  const int nd = s->ndim;
+  uint64_t numel = 1;
+  bool empty = false;
+  for (int d = 0; d < nd; ++d) {
+    const int64_t e = s->global_shape[d];
+    if (e < 0) return VESRNG_ERR_BAD_SHAPE;
+    if (e == 0) empty = true;
+  }
+  if (!empty)
+    for (int d = 0; d < nd; ++d) {
+      const uint64_t e = static_cast<uint64_t>(s->global_shape[d]);
+      if (numel > kMaxNumel / e) return VESRNG_ERR_BAD_SHAPE;
+      numel *= e;
+    }
+  else
+    numel = 0;
+
+  // Global strides (Algorithm 1's pi) and the largest flat index they reach.
+  std::vector<int64_t> pi(static_cast<size_t>(nd), 1);
+  if (s->global_stride) {
+    for (int d = 0; d < nd; ++d) {
+      if (s->global_stride[d] <= 0) return VESRNG_ERR_OVERFLOW;
+      pi[static_cast<size_t>(d)] = s->global_stride[d];
+    }
+  } else {
+    for (int d = nd - 1; d > 0; --d)
+      pi[static_cast<size_t>(d) - 1] =
+          pi[static_cast<size_t>(d)] * std::max<int64_t>(1, s->global_shape[d]);
+  }
+  uint64_t max_index = 0;
+  if (!empty)
+    for (int d = 0; d < nd; ++d) {
+      const uint64_t span = static_cast<uint64_t>(s->global_shape[d] - 1);
+      const uint64_t st = static_cast<uint64_t>(pi[static_cast<size_t>(d)]);
+      if (span != 0 && st > (kMaxNumel - max_index) / span) return VESRNG_ERR_OVERFLOW;
+      max_index += span * st;
+    }
+
+  for (int m = 0; m < s->mesh_ndim; ++m) {
+    if (s->mesh_shape[m] < 1) return VESRNG_ERR_BAD_MESH;
+  }
+  for (int m = 0; m < s->mesh_ndim; ++m) {
+    if (s->mesh_coord[m] < 0 || s->mesh_coord[m] >= s->mesh_shape[m]) return VESRNG_ERR_BAD_COORD;
+  }
+  for (int m = 0; m < s->mesh_ndim; ++m) {
+    const vesrng_placement& pl = s->placements[m];
+    if (pl.kind == VESRNG_REPLICATE) continue;
+    if (pl.kind != VESRNG_SHARD && pl.kind != VESRNG_INTERLEAVED_SHARD) return VESRNG_ERR_BAD_PLACEMENT;
+    if (pl.dim < 0 || pl.dim >= nd) return VESRNG_ERR_BAD_PLACEMENT;
+    if (pl.kind == VESRNG_INTERLEAVED_SHARD && pl.interleave < 1) return VESRNG_ERR_BAD_PLACEMENT;
+  }
+
+  std::vector<DimBox> boxes(static_cast<size_t>(nd));
+  for (int d = 0; d < nd; ++d) boxes[static_cast<size_t>(d)].subs.assign(1, Sub{s->global_shape[d], 1});
+  for (int m = 0; m < s->mesh_ndim; ++m) {
+    const vesrng_placement& pl = s->placements[m];
+    if (pl.kind == VESRNG_REPLICATE) continue;
+    DimBox& box = boxes[static_cast<size_t>(pl.dim)];
+    const vesrng_status st =
+        pl.kind == VESRNG_SHARD
+            ? apply_shard(box, s->mesh_shape[m], s->mesh_coord[m])
+            : apply_interleaved(box, pl.interleave, s->mesh_shape[m], s->mesh_coord[m]);
+    if (st != VESRNG_OK) return st;
+  }
+
+  g->local_shape.assign(static_cast<size_t>(nd), 0);
+  g->local_numel = 1;
+  for (int d = 0; d < nd; ++d) {
+    g->local_shape[static_cast<size_t>(d)] = boxes[static_cast<size_t>(d)].length();
+    g->local_numel *= g->local_shape[static_cast<size_t>(d)];
+  }
+  g->global_numel = numel;
+  g->max_global_index = max_index;
+  g->origin = 0;
+  g->axes.clear();
+  if (g->local_numel == 0) return VESRNG_OK;
+
+  std::vector<Axis> raw;
+  for (int d = 0; d < nd; ++d) {
+    const DimBox& box = boxes[static_cast<size_t>(d)];
+    const int64_t st = pi[static_cast<size_t>(d)];
+    g->origin += static_cast<uint64_t>(box.origin) * static_cast<uint64_t>(st);
+    for (const Sub& sub : box.subs)
+      if (sub.extent != 1) raw.push_back(Axis{sub.extent, sub.step * st});
+  }
+  // Merge neighbours that form one longer arithmetic progression.
+  for (const Axis& a : raw) {
+    if (!g->axes.empty() && g->axes.back().stride == a.extent * a.stride)
+      g->axes.back() = Axis{g->axes.back().extent * a.extent, a.stride};
+    else
+      g->axes.push_back(a);
+  }
+  if (g->axes.size() > static_cast<size_t>(kMaxOuter)) return VESRNG_ERR_UNSUPPORTED;
+  return VESRNG_OK;
+}
+
+RunShape run_shape(const Geometry& g) {
+  RunShape rs;
+  size_t n_outer = g.axes.size();
+  if (!g.axes.empty() && g.axes.back().stride == 1) {
+    rs.run_len = static_cast<uint64_t>(g.axes.back().extent);
+    --n_outer;
+  }
+  for (size_t k = n_outer; k-- > 0;) {
+    rs.outer.push_back(g.axes[k]);
+    rs.n_runs *= static_cast<uint64_t>(g.axes[k].extent);
+    if (g.axes[k].stride % 4 != 0) rs.phases_equal = false;
+  }
+  return rs;
+}
+
+bool fits_32bit(const RunShape& rs, uint64_t units_per_run) {
+  const uint64_t lim = 1ull << 31;
+  if (rs.run_len >= lim || units_per_run >= lim) return false;
+  if (rs.n_runs >= lim || rs.n_runs * units_per_run >= lim) return false;
+  // Local flat indices are formed as run * run_len + k in the index type.
+  if (rs.n_runs * rs.run_len >= lim) return false;
+  for (const Axis& a : rs.outer)
+    if (static_cast<uint64_t>(a.extent) >= lim) return false;
+  return true;
+}
+
+template <typename IT>
+PlanT<IT> make_plan(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run) {
+  PlanT<IT> p{};
+  p.pos0 = offset + g.origin;
+  p.total_units = units_per_run * rs.n_runs;
+  p.run_len = static_cast<IT>(rs.run_len);
+  p.units_per_run = static_cast<IT>(units_per_run);
+  p.units_div = DivOf<IT>::make(units_per_run);
+  p.n_outer = static_cast<int32_t>(rs.outer.size());
+  for (size_t k = 0; k < rs.outer.size(); ++k) {
+    p.outer_extent[k] = static_cast<IT>(rs.outer[k].extent);
+    p.outer_div[k] = DivOf<IT>::make(static_cast<uint64_t>(rs.outer[k].extent));
+    p.outer_stride[k] = static_cast<uint64_t>(rs.outer[k].stride);
+  }
+  for (size_t k = rs.outer.size(); k < static_cast<size_t>(kMaxOuter); ++k) {
+    p.outer_extent[k] = 1;
+    p.outer_div[k] = DivOf<IT>::make(1);
+    p.outer_stride[k] = 0;
+  }
+  return p;
+}
+
+template PlanT<uint32_t> make_plan<uint32_t>(const Geometry&, const RunShape&, uint64_t, uint64_t);
+template PlanT<uint64_t> make_plan<uint64_t>(const Geometry&, const RunShape&, uint64_t, uint64_t);
+
+}  // namespace vesrng

@@ -1,0 +1,97 @@
+// Decode plan: what the host hands to a kernel so that it can evaluate the
+// local-to-global index map of Algorithm 1 (veScale, Section 5) without reading
+// any metadata from memory.
+//
+// The rank's shard is described as a row-major box of "runs": the innermost
+// axis is a run of `run_len` elements that are consecutive both in the local
+// tensor and in the flattened global tensor; the outer axes enumerate the runs,
+// each with its own global stride.  Algorithm 1's per-element mixed-radix decode
+// (i' mod upsilon_d, i' / upsilon_d, sum of c_d * pi_d) is performed once per
+// run-unit instead of once per element, with divisions by launch constants
+// turned into multiply-shift.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define VESRNG_HD __host__ __device__ inline __attribute__((always_inline))
+#else
+#define VESRNG_HD inline
+#endif
+
+namespace vesrng {
+
+constexpr int kMaxOuter = 16;
+
+// 32x32 -> high 32 bits.
+VESRNG_HD uint32_t mul_hi_u32(uint32_t a, uint32_t b) {
+  return static_cast<uint32_t>((static_cast<uint64_t>(a) * b) >> 32);
+}
+
+// Division of a dividend n < 2^31 by a fixed divisor 1 <= d <= 2^31 with one
+// high multiply: q = (mulhi(n, m) + n) >> s, where s = ceil(log2 d) and
+// m = floor(2^32 (2^s - d) / d) + 1 (round-up method of Granlund & Montgomery).
+// n < 2^31 keeps the sum inside 32 bits.
+struct Div32 {
+  uint32_t d, m, s;
+  VESRNG_HD uint32_t div(uint32_t n) const { return (mul_hi_u32(n, m) + n) >> s; }
+};
+
+inline Div32 make_div32(uint32_t d) {
+  Div32 r;
+  r.d = d;
+  uint32_t s = 0;
+  while ((1ull << s) < d) ++s;
+  r.s = s;
+  r.m = static_cast<uint32_t>(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+  return r;
+}
+
+// Same interface on 64-bit indices, for shards too large for the 32-bit path.
+struct Div64 {
+  uint64_t d;
+  VESRNG_HD uint64_t div(uint64_t n) const { return n / d; }
+};
+
+template <typename IT>
+struct DivOf;
+template <>
+struct DivOf<uint32_t> {
+  using type = Div32;
+  static Div32 make(uint64_t d) { return make_div32(static_cast<uint32_t>(d)); }
+};
+template <>
+struct DivOf<uint64_t> {
+  using type = Div64;
+  static Div64 make(uint64_t d) { return Div64{d}; }
+};
+
+template <typename IT>
+struct PlanT {
+  using Div = typename DivOf<IT>::type;
+  uint64_t pos0;        // stream position of local element 0: offset + its global flat index
+  uint64_t total_units; // units_per_run * number of runs
+  IT run_len;           // elements per run
+  IT units_per_run;     // work units one run is cut into
+  Div units_div;        // divides by units_per_run
+  int32_t n_outer;      // axes that enumerate runs; axis 0 varies fastest
+  IT outer_extent[kMaxOuter];
+  Div outer_div[kMaxOuter];
+  uint64_t outer_stride[kMaxOuter]; // global stride of the axis, in elements
+};
+
+// Global offset (in elements, relative to local element 0) of run number `o`.
+template <typename IT>
+VESRNG_HD uint64_t run_offset(const PlanT<IT>& p, IT o) {
+  uint64_t off = 0;
+#pragma unroll 1
+  for (int k = 0; k + 1 < p.n_outer; ++k) {
+    const IT q = p.outer_div[k].div(o);
+    const IT c = o - q * p.outer_extent[k];
+    off += static_cast<uint64_t>(c) * p.outer_stride[k];
+    o = q;
+  }
+  if (p.n_outer > 0) off += static_cast<uint64_t>(o) * p.outer_stride[p.n_outer - 1];
+  return off;
+}
+
+}  // namespace vesrng

@@ -1,0 +1,248 @@
+// C ABI of the library: argument checking and marshalling only; every step of
+// the path (index decode, generator, conversion, stores) runs in the kernels.
+#include "../../include/vesrng.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <limits>
+
+#include "geometry.hpp"
+#include "launch.hpp"
+
+using namespace vesrng;
+
+namespace {
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+uint32_t f32_bits(float f) {
+  uint32_t b;
+  std::memcpy(&b, &f, sizeof b);
+  return b;
+}
+float f32_from_bits(uint32_t b) {
+  float f;
+  std::memcpy(&f, &b, sizeof f);
+  return f;
+}
+
+// fp32 -> bfloat16, round to nearest even (finite inputs).
+uint32_t bf16_rne(float f) {
+  const uint32_t b = f32_bits(f);
+  return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+float bf16_value(uint32_t h) { return f32_from_bits(h << 16); }
+
+// Largest bfloat16 strictly below `high` (bit pattern), high finite.
+uint32_t bf16_below(float high) {
+  uint32_t h = bf16_rne(high) & 0xFFFFu;
+  if (bf16_value(h) >= high) {
+    const float t = bf16_value(h);
+    if (t > 0.0f) h -= 1;
+    else if (t == 0.0f) h = 0x8001u;
+    else h += 1;
+  }
+  return h & 0xFFFFu;
+}
+
+// Checks shared by every generating entry point; fills geometry and the seed.
+vesrng_status prepare(const vesrng_sharding* s, uint64_t seed, uint64_t offset, Geometry* g, OpParams* prm) {
+  const vesrng_status st = build_geometry(s, g);
+  if (st != VESRNG_OK) return st;
+  if (offset % 4 != 0) return VESRNG_ERR_OFFSET_ALIGN;
+  // The last stream position the whole tensor uses must not wrap.
+  if (g->global_numel != 0 && offset > std::numeric_limits<uint64_t>::max() - g->max_global_index - 4)
+    return VESRNG_ERR_OVERFLOW;
+  prm->key0 = static_cast<uint32_t>(seed);
+  prm->key1 = static_cast<uint32_t>(seed >> 32);
+  return VESRNG_OK;
+}
+
+vesrng_status finish(hipError_t e) { return e == hipSuccess ? VESRNG_OK : VESRNG_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+vesrng_status vesrng_local_shape(const vesrng_sharding* s, int64_t* local_shape, int64_t* local_numel) {
+  if (!s || !local_numel) return VESRNG_ERR_NULL;
+  Geometry g;
+  const vesrng_status st = build_geometry(s, &g);
+  if (st != VESRNG_OK) return st;
+  if (local_shape)
+    for (size_t d = 0; d < g.local_shape.size(); ++d) local_shape[d] = g.local_shape[d];
+  *local_numel = g.local_numel;
+  return VESRNG_OK;
+}
+
+vesrng_status vesrng_advance_offset(const vesrng_sharding* s, uint64_t offset, uint64_t* new_offset) {
+  if (!s || !new_offset) return VESRNG_ERR_NULL;
+  if (offset % 4 != 0) return VESRNG_ERR_OFFSET_ALIGN;
+  // Only the global shape matters: use a one-rank view of the same tensor.
+  vesrng_sharding whole = *s;
+  whole.mesh_ndim = 0;
+  whole.mesh_shape = nullptr;
+  whole.placements = nullptr;
+  whole.mesh_coord = nullptr;
+  Geometry g;
+  const vesrng_status st = build_geometry(&whole, &g);
+  if (st != VESRNG_OK) return st;
+  // Draws consumed: one per position up to the last global element.
+  const uint64_t span = g.global_numel == 0 ? 0 : g.max_global_index + 1;
+  const uint64_t step = 4 * ((span + 3) / 4);
+  if (offset > std::numeric_limits<uint64_t>::max() - step) return VESRNG_ERR_OVERFLOW;
+  *new_offset = offset + step;
+  return VESRNG_OK;
+}
+
+vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int64_t* local_index,
+                                  uint64_t* global_index) {
+  if (!s || (n > 0 && (!local_index || !global_index))) return VESRNG_ERR_NULL;
+  Geometry g;
+  const vesrng_status st = build_geometry(s, &g);
+  if (st != VESRNG_OK) return st;
+  const RunShape rs = run_shape(g);
+  // Same plan types and decode routine as the kernels, compiled for the host.
+  const bool narrow = fits_32bit(rs, rs.run_len);
+  const PlanT<uint32_t> p32 = narrow ? make_plan<uint32_t>(g, rs, 0, rs.run_len) : PlanT<uint32_t>{};
+  const PlanT<uint64_t> p64 = make_plan<uint64_t>(g, rs, 0, rs.run_len);
+  for (int64_t k = 0; k < n; ++k) {
+    const int64_t i = local_index[k];
+    if (i < 0 || i >= g.local_numel) return VESRNG_ERR_BAD_PARAM;
+    if (narrow) {
+      const uint32_t w = static_cast<uint32_t>(i);
+      const uint32_t run = p32.units_div.div(w);
+      global_index[k] = p32.pos0 + run_offset(p32, run) + (w - run * p32.units_per_run);
+    } else {
+      const uint64_t w = static_cast<uint64_t>(i);
+      const uint64_t run = p64.units_div.div(w);
+      global_index[k] = p64.pos0 + run_offset(p64, run) + (w - run * p64.units_per_run);
+    }
+  }
+  return VESRNG_OK;
+}
+
+vesrng_status vesrng_raw_u32(const vesrng_sharding* s, uint64_t seed, uint64_t offset, uint32_t* out,
+                             void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!out) return VESRNG_ERR_NULL;
+  if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
+  return finish(launch_op(kOpRaw, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
+}
+
+vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, double low, double high,
+                             uint64_t seed, uint64_t offset, void* out, void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  const float lo = static_cast<float>(low), hi = static_cast<float>(high);
+  if (!(low <= high) || !std::isfinite(lo) || !std::isfinite(hi) || !std::isfinite(hi - lo))
+    return VESRNG_ERR_BAD_PARAM;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!out) return VESRNG_ERR_NULL;
+  if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
+  prm.dtype = dtype;
+  prm.low = lo;
+  prm.high = hi;
+  prm.width = hi - lo;
+  if (hi > lo) {
+    prm.top_f32 = std::nextafterf(hi, lo);
+    prm.top_bf16 = bf16_below(hi);
+  } else {
+    prm.top_f32 = hi;
+    prm.top_bf16 = bf16_rne(hi) & 0xFFFFu;
+  }
+  return finish(launch_op(kOpUniform, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
+}
+
+vesrng_status vesrng_normal(const vesrng_sharding* s, vesrng_dtype dtype, double mean, double std,
+                            uint64_t seed, uint64_t offset, void* out, void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  const float m = static_cast<float>(mean), sd = static_cast<float>(std);
+  if (!(std >= 0.0) || !std::isfinite(m) || !std::isfinite(sd)) return VESRNG_ERR_BAD_PARAM;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!out) return VESRNG_ERR_NULL;
+  if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
+  prm.dtype = dtype;
+  prm.mean = m;
+  prm.stddev = sd;
+  return finish(launch_op(kOpNormal, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
+}
+
+vesrng_status vesrng_dropout(const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
+                             uint64_t offset, const void* x, void* y, uint8_t* mask, void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  if (!(p >= 0.0 && p <= 1.0)) return VESRNG_ERR_BAD_PARAM;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!x || !y) return VESRNG_ERR_NULL;
+  if (misaligned(x, 16) || misaligned(y, 16) || misaligned(mask, 16)) return VESRNG_ERR_ALIGN;
+  prm.dtype = dtype;
+  // keep = (draw >> 8) < T with T = round((1 - p) 2^24), i.e. draw <= (T << 8) - 1 for T >= 1.
+  const uint64_t threshold = static_cast<uint64_t>(std::floor((1.0 - p) * 16777216.0 + 0.5));
+  prm.keep_any = threshold != 0 ? 1u : 0u;
+  prm.limit = threshold != 0 ? static_cast<uint32_t>((threshold << 8) - 1) : 0u;
+  prm.scale = static_cast<float>(1.0 / (1.0 - p));
+  return finish(launch_op(kOpDropout, g, offset, prm, x, y, mask, static_cast<hipStream_t>(hip_stream)));
+}
+
+vesrng_status vesrng_randint(const vesrng_sharding* s, int64_t low, int64_t high, uint64_t seed,
+                             uint64_t offset, int64_t* out, void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (high <= low) return VESRNG_ERR_BAD_PARAM;
+  const uint64_t range = static_cast<uint64_t>(high) - static_cast<uint64_t>(low);
+  if (range > (1ull << 32)) return VESRNG_ERR_BAD_PARAM;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!out) return VESRNG_ERR_NULL;
+  if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
+  prm.base = low;
+  prm.range = static_cast<uint32_t>(range);  // 2^32 -> 0
+  if (prm.range != 0) {
+    // q = floor(n / d) for any 32-bit n: s = ceil(log2 d), m = floor(2^32 (2^s - d) / d) + 1,
+    // t = mulhi(n, m), q = (t + ((n - t) >> 1)) >> (s - 1); d = 1 is handled as s = 0.
+    uint32_t sh = 0;
+    while ((1ull << sh) < range) ++sh;
+    prm.range_s = sh;
+    prm.range_m = static_cast<uint32_t>(((1ull << 32) * ((1ull << sh) - range)) / range + 1);
+  }
+  return finish(launch_op(kOpRandint, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
+}
+
+const char* vesrng_status_string(vesrng_status st) {
+  switch (st) {
+    case VESRNG_OK: return "ok";
+    case VESRNG_ERR_NULL: return "a required pointer is NULL";
+    case VESRNG_ERR_BAD_SHAPE: return "bad global shape";
+    case VESRNG_ERR_BAD_MESH: return "bad mesh shape";
+    case VESRNG_ERR_BAD_COORD: return "mesh coordinate out of range";
+    case VESRNG_ERR_BAD_PLACEMENT: return "bad placement";
+    case VESRNG_ERR_OFFSET_ALIGN: return "offset must be a multiple of 4";
+    case VESRNG_ERR_BAD_PARAM: return "bad operator parameter";
+    case VESRNG_ERR_DTYPE: return "unsupported dtype";
+    case VESRNG_ERR_UNSUPPORTED: return "sharding not decodable in closed form";
+    case VESRNG_ERR_OVERFLOW: return "stream position or stride overflow";
+    case VESRNG_ERR_HIP: return "HIP launch failed";
+    case VESRNG_ERR_ALIGN: return "device pointer not 16-byte aligned";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

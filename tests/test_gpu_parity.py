@@ -1,0 +1,396 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, element by element.  Bars: raw draws, uniforms, dropout outputs and masks and
+integers are bit-exact; fp32 normals within 1e-6 * max(|ref|, std) of the double-precision
+definition; bf16 normals within one bfloat16 ulp (neighbouring value)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_07003_amd as v
+from helpers import merge_shards, mesh_coords
+from paper_2509_07003_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+THREADS = min(16, os.cpu_count() or 1)
+DEV = "cuda"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ helpers ----
+def gpu_fill(op, dtype, sharding_args, seed, offset, **params):
+    """Runs one fill through the C ABI; returns a numpy array of the local shard
+    (uint32 raw, float32, uint16 bf16 bits or int64)."""
+    sh = v.Sharding(*sharding_args)
+    shape, n = v.vesrng_local_shape(sh)
+    if op == "raw":
+        out = torch.empty(max(n, 1), dtype=torch.int32, device=DEV)
+        v.vesrng_raw_u32(sh, seed, offset, out)
+        res = out.cpu().numpy().view(np.uint32)
+    elif op == "randint":
+        out = torch.empty(max(n, 1), dtype=torch.int64, device=DEV)
+        v.vesrng_randint(sh, params["low"], params["high"], seed, offset, out)
+        res = out.cpu().numpy()
+    else:
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        out = torch.empty(max(n, 1), dtype=tdt, device=DEV)
+        code = v.F32 if dtype == "f32" else v.BF16
+        if op == "uniform":
+            v.vesrng_uniform(sh, code, params.get("low", 0.0), params.get("high", 1.0), seed, offset, out)
+        else:
+            v.vesrng_normal(sh, code, params.get("mean", 0.0), params.get("std", 1.0), seed, offset, out)
+        res = out.cpu().numpy() if dtype == "f32" else out.view(torch.int16).cpu().numpy().view(np.uint16)
+    torch.cuda.synchronize()
+    return res[:n].reshape(shape)
+
+
+def gpu_dropout(dtype, sharding_args, p, seed, offset, x_np, with_mask=True, in_place=False):
+    sh = v.Sharding(*sharding_args)
+    shape, n = v.vesrng_local_shape(sh)
+    if dtype == "f32":
+        x = torch.from_numpy(np.ascontiguousarray(x_np, dtype=np.float32).reshape(-1)).to(DEV)
+    else:
+        x = torch.from_numpy(np.ascontiguousarray(x_np).reshape(-1).view(np.int16)).to(DEV).view(torch.bfloat16)
+    y = x if in_place else torch.empty_like(x)
+    mask = torch.full((max(n, 1),), 7, dtype=torch.uint8, device=DEV) if with_mask else None
+    v.vesrng_dropout(sh, v.F32 if dtype == "f32" else v.BF16, p, seed, offset, x, y, mask)
+    torch.cuda.synchronize()
+    yn = y.cpu().numpy() if dtype == "f32" else y.view(torch.int16).cpu().numpy().view(np.uint16)
+    return yn[:n].reshape(shape), (mask.cpu().numpy()[:n].reshape(shape) if with_mask else None)
+
+
+def bf16_ordinal(bits):
+    """Monotone integer code of bfloat16 bit patterns (+0 and -0 coincide)."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+def assert_float_bits_equal(got, want, what):
+    """Bit-exact, except that any NaN matches any NaN (payloads are unspecified)."""
+    if got.dtype == np.float32:
+        g, w = got.view(np.uint32), want.view(np.uint32)
+        nan_g, nan_w = np.isnan(got), np.isnan(want)
+    else:
+        g, w = got, want
+        nan_g = (got & 0x7F80) == 0x7F80
+        nan_g &= (got & 0x007F) != 0
+        nan_w = ((want & 0x7F80) == 0x7F80) & ((want & 0x007F) != 0)
+    assert np.array_equal(nan_g, nan_w), what + ": NaN positions differ"
+    bad = (g != w) & ~nan_g
+    assert not bad.any(), "%s: %d mismatches, first at %s" % (what, bad.sum(), np.argwhere(bad)[:3].tolist())
+
+
+def check_normal(got, sharding_args, dtype, mean, std, seed, offset, what, i_begin=0, i_end=-1):
+    ref = oracle.normal_f64_values(tuple(sharding_args), mean, std, seed, offset, i_begin=i_begin,
+                                   i_end=i_end, threads=THREADS).reshape(-1)
+    g = got.reshape(-1)
+    sl = slice(i_begin, None if i_end < 0 else i_end)
+    ref, g = ref[sl], g[sl]
+    if dtype == "f32":
+        err = np.abs(g.astype(np.float64) - ref)
+        tol = 1e-6 * np.maximum(np.abs(ref), std)
+        worst = float((err / tol).max()) if err.size else 0.0
+        assert worst <= 1.0, "%s: error is %.3f of the tolerance" % (what, worst)
+        return worst
+    # bfloat16: the kernel rounds an fp32 value that lies within the fp32 tolerance of the
+    # reference, so - rounding being monotone - its result must lie between the roundings of
+    # ref - tol and ref + tol.  Away from zero that is the reference value or its neighbour
+    # (one bfloat16 ulp); next to zero it also admits the other sign of a vanishing value.
+    tol = 1e-6 * np.maximum(np.abs(ref), std)
+    lo = bf16_ordinal(_bf16_bits(ref - tol))
+    hi = bf16_ordinal(_bf16_bits(ref + tol))
+    go = bf16_ordinal(g)
+    bad = (go < lo) | (go > hi)
+    assert not bad.any(), "%s: %d values outside the rounding interval, first %s" % (what, bad.sum(), np.argwhere(bad)[:3].tolist())
+    assert (hi - lo)[np.abs(ref) > 1e-3 * std].max(initial=0) <= 1
+    want = oracle.normal(tuple(sharding_args), oracle.BF16, mean, std, seed, offset, i_begin=i_begin,
+                         i_end=i_end, threads=THREADS).reshape(-1)[sl]
+    return float((g != want).mean()) if g.size else 0.0
+
+
+def _bf16_bits(a64):
+    t = torch.from_numpy(np.ascontiguousarray(a64)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+# ------------------------------------------------------------- the configs ----
+def test_c1_uniform_f32_row_shards_bit_exact():
+    w = W.C1
+    shards = {}
+    for c in mesh_coords(w.mesh_shape):
+        say("C1 rank %s" % (c,))
+        args = w.sharding_args(c)
+        got = gpu_fill("uniform", "f32", args, w.seed, 0)
+        want = oracle.uniform(tuple(args), oracle.F32, 0.0, 1.0, w.seed, 0, threads=THREADS)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        raw = gpu_fill("raw", None, args, w.seed, 0)
+        assert np.array_equal(raw, oracle.raw_u32(tuple(args), w.seed, 0, threads=THREADS))
+        shards[c] = got
+    single = gpu_fill("uniform", "f32", (w.global_shape, [1], [("R",)], [0]), w.seed, 0)
+    assert np.array_equal(merge_shards(shards, w.mesh_shape, w.placements), single)
+    # The first worked values of this configuration (see tests/golden/worked_values.txt).
+    assert single.reshape(-1)[0] == np.float32(0.1272079348564148)
+    assert shards[(1,)].reshape(-1)[0] == np.float32(0.630875825881958)
+
+
+def test_c2_normal_f32_ragged_column_shards_and_offset_progression():
+    w = W.C2
+    sh_any = v.Sharding(*w.sharding_args([0]))
+    off2 = v.vesrng_advance_offset(sh_any, 0)
+    assert off2 == 4096 * 4096
+    for call, off in enumerate((0, off2)):
+        shards = {}
+        for c in mesh_coords(w.mesh_shape):
+            say("C2 call %d rank %s" % (call, c))
+            args = w.sharding_args(c)
+            got = gpu_fill("normal", "f32", args, w.seed, off)
+            worst = check_normal(got, args, "f32", 0.0, 1.0, w.seed, off, "C2 call %d rank %s" % (call, c))
+            say("  worst error / tolerance = %.3f" % worst)
+            raw = gpu_fill("raw", None, args, w.seed, off)
+            assert np.array_equal(raw, oracle.raw_u32(tuple(args), w.seed, off, threads=THREADS))
+            shards[c] = got
+        assert [s.shape[1] for s in shards.values()] == [1366, 1366, 1364]
+        single = gpu_fill("normal", "f32", (w.global_shape, [1], [("R",)], [0]), w.seed, off)
+        merged = merge_shards(shards, w.mesh_shape, w.placements)
+        assert np.array_equal(merged.view(np.uint32), single.view(np.uint32))   # bit-wise on the GPU itself
+        if call == 1:
+            # Second call == elements [2^24, 2^25) of a 1-D stream of 2^25 elements at offset 0.
+            both = gpu_fill("normal", "f32", ([2 * off2], [1], [("R",)], [0]), w.seed, 0)
+            assert np.array_equal(both[off2:].view(np.uint32), single.reshape(-1).view(np.uint32))
+            assert not np.array_equal(both[:off2].view(np.uint32), single.reshape(-1).view(np.uint32))
+
+
+def test_c3_normal_bf16_weight_init_2d_mesh():
+    w = W.C3
+    shards = {}
+    for c in mesh_coords(w.mesh_shape):
+        say("C3 rank %s" % (c,))
+        args = w.sharding_args(c)
+        got = gpu_fill("normal", "bf16", args, w.seed, 0, mean=0.0, std=0.02)
+        assert got.shape == (2048, 3584)
+        frac = check_normal(got, args, "bf16", 0.0, 0.02, w.seed, 0, "C3 rank %s" % (c,))
+        say("  fraction not equal to the rounded reference = %.2e" % frac)
+        shards[c] = got
+    single = gpu_fill("normal", "bf16", (w.global_shape, [1], [("R",)], [0]), w.seed, 0, mean=0.0, std=0.02)
+    assert np.array_equal(merge_shards(shards, w.mesh_shape, w.placements), single)
+    vals = torch.from_numpy(single.view(np.int16)).view(torch.bfloat16).float()
+    assert abs(float(vals.mean())) < 1e-4 and abs(float(vals.std()) - 0.02) < 2e-4
+
+
+def test_c4_dropout_bf16_sequence_sharded():
+    w = W.C4
+    for c in mesh_coords(w.mesh_shape):
+        say("C4 rank %s" % (c,))
+        args = w.sharding_args(c)
+        x = W.host_activations([8, 512, 4096], w.input_seed + c[0], "normal", "bf16")
+        y, m = gpu_dropout("bf16", args, 0.1, w.seed, 0, x)
+        yo, mo = oracle.dropout(tuple(args), oracle.BF16, 0.1, w.seed, 0, x, threads=THREADS)
+        assert np.array_equal(m, mo)
+        assert_float_bits_equal(y, yo, "C4 rank %s" % (c,))
+        assert abs(m.mean() - 0.9) < 1e-3
+
+
+def _c5_check(w, coord):
+    args = w.sharding_args(coord)
+    shape, n = v.vesrng_local_shape(v.Sharding(*args))
+    assert shape == [8, 4, 4096, 4096]
+    say("%s: making input on the device" % w.name)
+    x = W.device_activations(shape, w.input_seed, "softmax", "bf16").reshape(-1)
+    y = torch.empty_like(x)
+    mask = torch.empty(n, dtype=torch.uint8, device=DEV)
+    say("  launching")
+    v.vesrng_dropout(v.Sharding(*args), v.BF16, 0.1, w.seed, 0, x, y, mask)
+    torch.cuda.synchronize()
+    xh = x.view(torch.int16).cpu().numpy().view(np.uint16)
+    yh = y.view(torch.int16).cpu().numpy().view(np.uint16)
+    mh = mask.cpu().numpy()
+    # Whole-shard properties, then element-by-element parity on sampled ranges that
+    # include both ends and the seams between the non-contiguous slabs.
+    assert abs(mh.mean() - 0.899999976) < 5.2e-5
+    assert not yh[mh == 0].any()
+    slab = n // 8
+    ranges = [(0, 1 << 20), (n - (1 << 20), n)]
+    ranges += [(k * slab - (1 << 18), k * slab + (1 << 18)) for k in (1, 4, 7)]
+    ranges += [((1 << 24) * 5 - 4096, (1 << 24) * 5 + 4096), (n // 3, n // 3 + (1 << 20))]
+    for b, e in ranges:
+        say("  oracle on [%d, %d)" % (b, e))
+        yo, mo = oracle.dropout(tuple(args), oracle.BF16, 0.1, w.seed, 0, xh, i_begin=b, i_end=e, threads=THREADS)
+        assert np.array_equal(mh[b:e], mo.reshape(-1)[b:e])
+        assert_float_bits_equal(yh[b:e], yo.reshape(-1)[b:e], "%s [%d,%d)" % (w.name, b, e))
+
+
+def test_c5_dropout_bf16_attention_probabilities_nested_shard_full_size():
+    _c5_check(W.C5, W.C5.bench_coord)
+
+
+def test_c5_dropout_bf16_interleaved_reading_full_size():
+    _c5_check(W.C5_INTERLEAVED, W.C5_INTERLEAVED.bench_coord)
+
+
+# ------------------------------------------------- scaled operator matrix -----
+GRID_SHAPES = {1: [100003], 2: [301, 333], 3: [37, 53, 51], 4: [11, 13, 14, 50], 5: [7, 6, 9, 10, 22]}
+
+
+def _grid_cases():
+    for nd, shape in GRID_SHAPES.items():
+        for d in range(nd):
+            yield shape, [3], [("S", d)]
+        for a, b in itertools.product(range(nd), repeat=2):
+            yield shape, [2, 3], [("S", a), ("S", b)]
+
+
+@pytest.mark.parametrize("op,dtype", [("raw", None), ("uniform", "f32"), ("uniform", "bf16"), ("normal", "f32"),
+                                       ("normal", "bf16"), ("dropout", "f32"), ("dropout", "bf16"),
+                                       ("randint", None)])
+def test_operator_matrix_1d_to_5d_single_and_double_sharding(op, dtype):
+    """Scaled version of the paper's per-operator table: every operator, 1-D to 5-D tensors,
+    sharding on every dimension and every ordered pair of dimensions, odd extents."""
+    seed, offset = 0x5EED0001CAFE, 1 << 34    # exercises both key words and the high counter word
+    count = 0
+    for shape, mesh, pls in _grid_cases():
+        for c in mesh_coords(mesh):
+            args = (shape, mesh, pls, list(c))
+            what = "%s %s %s %s %s" % (op, dtype, shape, pls, c)
+            say(what)
+            targs = tuple(args)
+            if op == "raw":
+                assert np.array_equal(gpu_fill("raw", None, args, seed, offset), oracle.raw_u32(targs, seed, offset)), what
+            elif op == "randint":
+                got = gpu_fill("randint", None, args, seed, offset, low=-5, high=1000003)
+                assert np.array_equal(got, oracle.randint(targs, -5, 1000003, seed, offset)), what
+            elif op == "uniform":
+                got = gpu_fill("uniform", dtype, args, seed, offset, low=-2.5, high=7.25)
+                want = oracle.uniform(targs, oracle.F32 if dtype == "f32" else oracle.BF16, -2.5, 7.25, seed, offset)
+                assert_float_bits_equal(got, want, what)
+            elif op == "normal":
+                got = gpu_fill("normal", dtype, args, seed, offset, mean=1.5, std=0.25)
+                check_normal(got, args, dtype, 1.5, 0.25, seed, offset, what)
+            else:
+                n = oracle.local_shape(*args)[1]
+                xf = W.adversarial_f32(n, seed=count)
+                x = xf if dtype == "f32" else W.bf16_bits_from_f32(xf)
+                y, m = gpu_dropout(dtype, args, 0.3, seed, offset, x)
+                yo, mo = oracle.dropout(targs, oracle.F32 if dtype == "f32" else oracle.BF16, 0.3, seed, offset, x)
+                assert np.array_equal(m, mo), what
+                assert_float_bits_equal(y, yo, what)
+            count += 1
+    assert count > 300
+
+
+def test_gpu_shards_merge_to_the_gpu_single_device_tensor_bitwise():
+    """The paper's invariant on the product itself, including normals (bit-wise)."""
+    seed, offset = 99, 8
+    for shape, mesh, pls in [([129, 131], [2, 2], [("S", 0), ("S", 1)]), ([64, 66], [4], [("S", 1)]),
+                             ([12, 40, 9], [2, 3], [("S", 1), ("S", 1)]), ([6, 32, 10], [8], [("IS", 1, 4)]),
+                             ([48, 10], [2, 2], [("IS", 0, 4), ("R",)])]:
+        for op, dtype in (("normal", "f32"), ("normal", "bf16"), ("uniform", "bf16"), ("raw", None)):
+            shards = {c: gpu_fill(op, dtype, (shape, mesh, pls, list(c)), seed, offset) for c in mesh_coords(mesh)}
+            single = gpu_fill(op, dtype, (shape, [1], [("R",)], [0]), seed, offset)
+            merged = merge_shards(shards, mesh, pls)
+            assert merged.tobytes() == single.tobytes(), (shape, mesh, pls, op, dtype)
+
+
+# ------------------------------------------------------------ edge cases ------
+def test_tiny_empty_and_zero_dim_tensors():
+    for n in list(range(0, 10)) + [15, 16, 17, 31, 33]:
+        args = ([n], [1], [("R",)], [0])
+        assert np.array_equal(gpu_fill("raw", None, args, 5, 4), oracle.raw_u32(args, 5, 4))
+        got = gpu_fill("uniform", "bf16", args, 5, 4)
+        assert np.array_equal(got, oracle.uniform(args, oracle.BF16, 0.0, 1.0, 5, 4))
+    # More ranks than rows: ranks 2 and 3 of 4 hold nothing of 2 rows.
+    for r in range(4):
+        args = ([2, 5], [4], [("S", 0)], [r])
+        got = gpu_fill("uniform", "f32", args, 5, 0)
+        assert np.array_equal(got, oracle.uniform(args, oracle.F32, 0.0, 1.0, 5, 0))
+        assert got.size == (5 if r < 2 else 0)
+    zero_d = ([], [2], [("R",)], [1])
+    assert np.array_equal(gpu_fill("raw", None, zero_d, 5, 0), oracle.raw_u32(zero_d, 5, 0))
+    # Unsharded dimension of extent 1 and a column shard one element wide.
+    for args in (([5, 1, 7], [2], [("S", 2)], [1]), ([64, 3], [3], [("S", 1)], [2])):
+        assert np.array_equal(gpu_fill("raw", None, args, 5, 0), oracle.raw_u32(args, 5, 0))
+
+
+def test_uniform_bounds_and_upper_guard():
+    n = 1 << 16
+    args = ([n], [1], [("R",)], [0])
+    for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16)):
+        for low, high in ((0.0, 1.0), (-1.0, 1.0), (0.0, 3.0), (5.0, 5.0), (-0.02, 0.02), (1e-3, 1.0 + 1e-3)):
+            got = gpu_fill("uniform", dtype, args, 77, 0, low=low, high=high)
+            want = oracle.uniform(args, code, low, high, 77, 0)
+            assert_float_bits_equal(got, want, "uniform %s [%g,%g)" % (dtype, low, high))
+            vals = got if dtype == "f32" else torch.from_numpy(got.view(np.int16)).view(torch.bfloat16).float().numpy()
+            # bfloat16 cannot represent every low: the bound below is low rounded to the dtype.
+            floor = np.float32(low) if dtype == "f32" else np.float32(oracle.float_from_bf16(oracle.bf16_from_float(low)))
+            assert vals.min() >= floor and (vals.max() < np.float32(high) or low == high)
+
+
+def test_dropout_degenerate_probabilities_special_values_in_place_and_no_mask():
+    n = 4096 + 5
+    args = ([n], [1], [("R",)], [0])
+    xf = W.adversarial_f32(n, 4)
+    for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16)):
+        x = xf if dtype == "f32" else W.bf16_bits_from_f32(xf)
+        for p in (0.0, 1.0, 0.1, 0.5, 0.999999, 1e-9):
+            yo, mo = oracle.dropout(args, code, p, 3, 0, x)
+            y, m = gpu_dropout(dtype, args, p, 3, 0, x)
+            assert np.array_equal(m, mo), (dtype, p)
+            assert_float_bits_equal(y, yo, "dropout %s p=%g" % (dtype, p))
+            y2, _ = gpu_dropout(dtype, args, p, 3, 0, x, with_mask=False, in_place=True)
+            assert_float_bits_equal(y2, yo, "dropout in place %s p=%g" % (dtype, p))
+        y, m = gpu_dropout(dtype, args, 0.0, 3, 0, x)
+        assert y.tobytes() == np.ascontiguousarray(x).tobytes() and m.all()      # p = 0 is the identity, bit for bit
+        y, m = gpu_dropout(dtype, args, 1.0, 3, 0, x)
+        assert not y.view(np.uint8).any() and not m.any()                         # p = 1 writes +0 everywhere
+
+
+def test_randint_ranges():
+    args = ([1 << 15], [2], [("S", 0)], [1])
+    for low, high in ((0, 1), (0, 2), (-3, 4), (10, 10 + (1 << 31)), (0, 1 << 32), (-(1 << 40), -(1 << 40) + 4294967295)):
+        got = gpu_fill("randint", None, args, 8, 0, low=low, high=high)
+        assert np.array_equal(got, oracle.randint(args, low, high, 8, 0)), (low, high)
+
+
+def test_launch_on_a_side_stream():
+    args = ([1 << 18], [1], [("R",)], [0])
+    s = torch.cuda.Stream()
+    out = torch.empty(1 << 18, dtype=torch.float32, device=DEV)
+    with torch.cuda.stream(s):
+        v.vesrng_uniform(v.Sharding(*args), v.F32, 0.0, 1.0, 6, 0, out)
+    s.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.uniform(args, oracle.F32, 0.0, 1.0, 6, 0, threads=THREADS))
+
+
+def test_wide_index_path_beyond_2_to_31_local_elements():
+    """Local shards with more than 2^31 elements take the 64-bit index kernels; the paper's
+    table goes up to 16 GB tensors.  Parity on sampled ranges (the oracle is scalar)."""
+    # Unsharded [65537, 65536] fp32 = 2^32 + 65536 elements (16 GiB): one run, aligned kernel.
+    # (Two dimensions keep the oracle's explicit index lists short.)
+    shape = [65537, 65536]
+    n = shape[0] * shape[1]
+    args = (shape, [1], [("R",)], [0])
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    say("wide: 16 GiB uniform fill")
+    v.vesrng_uniform(v.Sharding(*args), v.F32, 0.0, 1.0, 21, 0, out)
+    torch.cuda.synchronize()
+    for b, e in ((0, 4096), ((1 << 31) - 2048, (1 << 31) + 2048), ((1 << 32) - 2048, (1 << 32) + 2048), (n - 4096, n)):
+        want = oracle.uniform(args, oracle.F32, 0.0, 1.0, 21, 0, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(out[b:e].cpu().numpy(), want), (b, e)
+    del out
+    # 2-D column shard, ragged (odd origin and width), 2^31 + ... local elements of raw draws.
+    shape, mesh, pls, c = [(1 << 15) + 1, (1 << 17) + 6], [2], [("S", 1)], [1]
+    args = (shape, mesh, pls, c)
+    lshape, ln = v.vesrng_local_shape(v.Sharding(*args))
+    assert ln > 1 << 31 and lshape[1] % 4 != 0
+    out = torch.empty(ln, dtype=torch.int32, device=DEV)
+    say("wide: ragged raw fill of %d elements" % ln)
+    v.vesrng_raw_u32(v.Sharding(*args), 22, 1 << 36, out)
+    torch.cuda.synchronize()
+    for b, e in ((0, 8192), (ln // 2 - 4096, ln // 2 + 4096), (ln - 8192, ln)):
+        want = oracle.raw_u32(args, 22, 1 << 36, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(out[b:e].cpu().numpy().view(np.uint32), want), (b, e)

@@ -1,0 +1,181 @@
+"""Host-side checks of the library (no GPU): the shared object loads and exports what
+include/vesrng.h declares, its closed-form shard geometry and kernel decode plan agree
+with the oracle's simulated index lists, and every error path returns its status."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2509_07003_amd as v
+from helpers import all_placements, mesh_coords
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vesrng.h")).read()
+    declared = sorted(set(re.findall(r"\b(vesrng_[a-z0-9_]+)\s*\(", header)))
+    assert {"vesrng_uniform", "vesrng_normal", "vesrng_dropout", "vesrng_advance_offset",
+            "vesrng_local_shape", "vesrng_raw_u32", "vesrng_randint", "vesrng_global_index",
+            "vesrng_status_string"} <= set(declared)
+    lib = ctypes.CDLL(v.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    for st in range(13):
+        assert v.vesrng_status_string(st) and "unknown" not in v.vesrng_status_string(st)
+    assert "unknown" in v.vesrng_status_string(99)
+
+
+SHAPES = [[1], [7], [12], [2, 6], [6, 4], [5, 3], [3, 4, 2], [4, 6, 3], [2, 3, 2, 4], [1, 6, 1, 3]]
+MESHES = [[1], [2], [3], [4], [2, 2], [2, 3], [3, 2], [4, 2], [2, 2, 2]]
+
+
+def test_geometry_and_decode_plan_match_the_oracle_brute_force():
+    supported = unsupported = 0
+    for shape in SHAPES:
+        for mesh in MESHES:
+            for pls in all_placements(len(shape), len(mesh)):
+                for c in mesh_coords(mesh):
+                    try:
+                        want_shape, want_n = oracle.local_shape(shape, mesh, list(pls), list(c))
+                    except oracle.OracleError:
+                        with pytest.raises(v.VesrngError) as e:
+                            v.vesrng_local_shape(v.Sharding(shape, mesh, pls, c))
+                        # (an earlier mesh dimension may already be out of closed-form reach)
+                        assert e.value.status in (5, 9)
+                        continue
+                    sh = v.Sharding(shape, mesh, pls, c)
+                    try:
+                        got_shape, got_n = v.vesrng_local_shape(sh)
+                    except v.VesrngError as e:
+                        # Only an interleaved dimension that is cut again may be out of reach.
+                        assert e.status == 9 and any(p[0] == "IS" for p in pls), (shape, mesh, pls, c)
+                        unsupported += 1
+                        continue
+                    supported += 1
+                    assert (got_shape, got_n) == (want_shape, want_n), (shape, mesh, pls, c)
+                    if want_n:
+                        want_j = oracle.global_indices(shape, mesh, list(pls), list(c)).reshape(-1)
+                        got_j = v.vesrng_global_index(sh, range(want_n))
+                        assert list(want_j) == got_j, (shape, mesh, pls, c)
+    assert supported > 20000 and unsupported < supported // 10
+
+
+def test_plain_shard_and_replicate_are_always_supported():
+    rng = np.random.default_rng(17)
+    for _ in range(300):
+        nd = int(rng.integers(1, 6))
+        shape = [int(x) for x in rng.integers(1, 12, size=nd)]
+        md = int(rng.integers(1, 4))
+        mesh = [int(x) for x in rng.integers(1, 6, size=md)]
+        pls = [("S", int(rng.integers(0, nd))) if rng.random() < 0.75 else ("R",) for _ in range(md)]
+        c = [int(rng.integers(0, p)) for p in mesh]
+        sh = v.Sharding(shape, mesh, pls, c)
+        want_shape, want_n = oracle.local_shape(shape, mesh, pls, c)
+        assert v.vesrng_local_shape(sh) == (want_shape, want_n)
+        if want_n:
+            want_j = oracle.global_indices(shape, mesh, pls, c).reshape(-1)
+            assert v.vesrng_global_index(sh, range(want_n)) == list(want_j)
+
+
+def test_global_stride_is_honoured():
+    shape, stride = [3, 4, 5], [1, 3, 12]      # a permuted (column-major) global view
+    for c in range(2):
+        sh = v.Sharding(shape, [2], [("S", 1)], [c], global_stride=stride)
+        n = v.vesrng_local_shape(sh)[1]
+        want = oracle.global_indices(shape, [2], [("S", 1)], [c], global_stride=stride).reshape(-1)
+        assert v.vesrng_global_index(sh, range(n)) == list(want)
+
+
+def test_wide_index_path_on_a_tensor_beyond_32_bits():
+    # 2^34 elements, column-sharded so that runs do not merge; indices need 64 bits.
+    shape, mesh, pls, c = [1 << 14, 1 << 20], [4, 2], [("S", 1), ("S", 0)], [3, 1]
+    sh = v.Sharding(shape, mesh, pls, c)
+    lshape, n = v.vesrng_local_shape(sh)
+    assert lshape == [1 << 13, 1 << 18] and n == 1 << 31
+    rows = oracle.index_list(shape, mesh, pls, c, 0)
+    cols = oracle.index_list(shape, mesh, pls, c, 1)
+    rng = np.random.default_rng(1)
+    idx = [0, n - 1, (1 << 18) - 1, 1 << 18] + [int(x) for x in rng.integers(0, n, size=200)]
+    want = [int(rows[i >> 18]) * (1 << 20) + int(cols[i & ((1 << 18) - 1)]) for i in idx]
+    assert v.vesrng_global_index(sh, idx) == want
+    assert max(want) >= 1 << 33
+
+
+def test_config_shards():
+    assert v.vesrng_local_shape(v.Sharding([4096, 4096], [3], [("S", 1)], [2])) == ([4096, 1364], 4096 * 1364)
+    assert v.vesrng_local_shape(v.Sharding([8, 32, 4096, 4096], [4, 2], [("S", 1), ("S", 1)], [3, 1])) == \
+        ([8, 4, 4096, 4096], 1 << 29)
+    sh = v.Sharding([8, 32, 4096, 4096], [4, 2], [("S", 1), ("S", 1)], [3, 1])
+    assert v.vesrng_global_index(sh, [0, (1 << 26) - 1, 1 << 26]) == \
+        [28 << 24, (32 << 24) - 1, (32 << 24) + (28 << 24)]
+    assert v.vesrng_local_shape(v.Sharding([3, 5], [4], [("S", 0)], [3])) == ([0, 5], 0)   # empty shard
+    assert v.vesrng_local_shape(v.Sharding([], [2], [("R",)], [1])) == ([], 1)             # 0-d tensor
+
+
+def test_advance_offset():
+    for shape, off in (([4096, 4096], 0), ([5], 8), ([8], 8), ([3, 3], 0), ([], 4), ([0, 9], 4), ([1 << 20, 1 << 14], 1 << 40)):
+        sh = v.Sharding(shape, [2], [("S", 0)] if shape else [("R",)], [1])
+        assert v.vesrng_advance_offset(sh, off) == oracle.advance_offset(shape, off)
+    # The same for every rank, whatever the placement.
+    a = v.vesrng_advance_offset(v.Sharding([10, 10], [4], [("S", 1)], [0]), 16)
+    b = v.vesrng_advance_offset(v.Sharding([10, 10], [2, 2], [("R",), ("S", 0)], [1, 1]), 16)
+    assert a == b == 116
+    with pytest.raises(v.VesrngError) as e:
+        v.vesrng_advance_offset(v.Sharding([10]), 3)
+    assert e.value.status == 6
+    with pytest.raises(v.VesrngError) as e:
+        v.vesrng_advance_offset(v.Sharding([1 << 40]), (1 << 64) - 8)
+    assert e.value.status == 10
+
+
+def _status(fn, *args):
+    with pytest.raises(v.VesrngError) as e:
+        fn(*args)
+    return e.value.status
+
+
+def test_error_paths_return_their_status_without_touching_the_gpu():
+    ok = v.Sharding([8, 8], [2], [("S", 0)], [0])
+    buf = 1 << 20   # a fake, 16-byte aligned device address: never dereferenced on an error path
+    assert _status(v.vesrng_local_shape, v.Sharding([4, -1])) == 2
+    assert _status(v.vesrng_local_shape, v.Sharding([2] * 9)) == 2
+    assert _status(v.vesrng_local_shape, v.Sharding([1 << 40, 1 << 40])) == 2
+    assert _status(v.vesrng_local_shape, v.Sharding([4], [0], [("S", 0)], [0])) == 3
+    assert _status(v.vesrng_local_shape, v.Sharding([4], [2], [("S", 0)], [2])) == 4
+    assert _status(v.vesrng_local_shape, v.Sharding([4], [2], [("S", 0)], [-1])) == 4
+    assert _status(v.vesrng_local_shape, v.Sharding([4], [2], [("P",)], [0])) == 5
+    assert _status(v.vesrng_local_shape, v.Sharding([4], [2], [("S", 1)], [0])) == 5
+    assert _status(v.vesrng_local_shape, v.Sharding([6], [2], [("IS", 0, 4)], [0])) == 5
+    assert _status(v.vesrng_local_shape, v.Sharding([6], [2], [("IS", 0, 0)], [0])) == 5
+    assert _status(v.vesrng_local_shape, v.Sharding([4, 4], global_stride=[4, 0])) == 10
+    assert _status(v.vesrng_uniform, ok, v.F32, 0.0, 1.0, 1, 2, buf) == 6
+    assert _status(v.vesrng_uniform, ok, v.F32, 2.0, 1.0, 1, 0, buf) == 7
+    assert _status(v.vesrng_uniform, ok, v.F32, 0.0, float("inf"), 1, 0, buf) == 7
+    assert _status(v.vesrng_uniform, ok, v.F32, float("nan"), 1.0, 1, 0, buf) == 7
+    assert _status(v.vesrng_uniform, ok, 7, 0.0, 1.0, 1, 0, buf) == 8
+    assert _status(v.vesrng_uniform, ok, v.F32, 0.0, 1.0, 1, 0, None) == 1
+    assert _status(v.vesrng_uniform, ok, v.F32, 0.0, 1.0, 1, 0, buf + 4) == 12
+    assert _status(v.vesrng_uniform, ok, v.F32, 0.0, 1.0, 1, (1 << 64) - 16, buf) == 10
+    assert _status(v.vesrng_normal, ok, v.F32, 0.0, -1.0, 1, 0, buf) == 7
+    assert _status(v.vesrng_normal, ok, v.BF16, float("nan"), 1.0, 1, 0, buf) == 7
+    assert _status(v.vesrng_normal, ok, 2, 0.0, 1.0, 1, 0, buf) == 8
+    assert _status(v.vesrng_dropout, ok, v.BF16, 1.5, 1, 0, buf, buf, None) == 7
+    assert _status(v.vesrng_dropout, ok, v.BF16, -0.1, 1, 0, buf, buf, None) == 7
+    assert _status(v.vesrng_dropout, ok, v.BF16, 0.1, 1, 0, None, buf, None) == 1
+    assert _status(v.vesrng_dropout, ok, v.BF16, 0.1, 1, 0, buf, buf, buf + 1) == 12
+    assert _status(v.vesrng_dropout, ok, v.BF16, 0.1, 1, 1, buf, buf, None) == 6
+    assert _status(v.vesrng_randint, ok, 5, 5, 1, 0, buf) == 7
+    assert _status(v.vesrng_randint, ok, 0, (1 << 32) + 1, 1, 0, buf) == 7
+    assert _status(v.vesrng_raw_u32, ok, 1, 0, None) == 1
+    assert _status(v.vesrng_raw_u32, v.Sharding([4], [2], [("P",)], [0]), 1, 0, buf) == 5
+    # Empty shard: fine, nothing to launch, pointers not needed.
+    v.vesrng_uniform(v.Sharding([3, 5], [4], [("S", 0)], [3]), v.F32, 0.0, 1.0, 1, 0, None)
+    v.vesrng_dropout(v.Sharding([0]), v.BF16, 0.1, 1, 0, None, None, None)
