@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the sharded-RNG hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: the fused dropout
+of workload C5 (bf16 attention probabilities, global [8,32,4096,4096], nested 2-D mesh 4x2
+with the head dimension sharded on both mesh dimensions) for ONE rank's [8,4,4096,4096]
+share - shard geometry and decode plan on the host, then index decode, Philox4x32-10,
+mask, scale and stores in one kernel - followed by the host-side offset advance.  Inputs
+are resident in HBM before the timed region.  The metric is algorithmic bytes per second
+(2 B read + 2 B written + 1 B mask per element).
+
+Prints ONE JSON line.  Only one GPU is used: --gpus above 1 is refused.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published peak HBM bandwidth
+
+
+def algorithmic_bytes(op, dtype, numel):
+    """Bytes the method itself must move per launch: fills write one element each; dropout
+    reads x and writes y and the one-byte mask."""
+    size = 4 if dtype == "f32" else 2
+    return numel * (2 * size + 1 if op == "dropout" else size)
+
+
+def read_traffic(workload_tag):
+    """HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), taken
+    from the committed profile summary, or None when no such summary exists."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload_tag)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def make_launcher(v, W, torch, w, coord, copies=1):
+    """Returns (launch(k), numel, algorithmic bytes) for workload w on rank `coord`.
+    `copies` distinct buffer sets are cycled so that small shards do not sit in cache."""
+    sh = v.Sharding(*w.sharding_args(coord))
+    shape, n = v.vesrng_local_shape(sh)
+    code = v.F32 if w.dtype == "f32" else v.BF16
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    outs = [torch.empty(n, dtype=tdt, device="cuda") for _ in range(copies)]
+    if w.op == "dropout":
+        xs = [W.device_activations(shape, w.input_seed + k, w.input_kind, w.dtype).reshape(-1) for k in range(copies)]
+        masks = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(copies)]
+    state = {"offset": w.offset}
+
+    def launch(k):
+        i = k % copies
+        off = state["offset"]
+        if w.op == "uniform":
+            v.vesrng_uniform(sh, code, w.params["low"], w.params["high"], w.seed, off, outs[i])
+        elif w.op == "normal":
+            v.vesrng_normal(sh, code, w.params["mean"], w.params["std"], w.seed, off, outs[i])
+        else:
+            v.vesrng_dropout(sh, code, w.params["p"], w.seed, off, xs[i], outs[i], masks[i])
+        state["offset"] = v.vesrng_advance_offset(sh, off)   # every rank steps by the global size
+
+    return launch, n, algorithmic_bytes(w.op, w.dtype, n)
+
+
+def time_kernel(torch, launch, steps, warmup):
+    """Average launch duration from HIP events recorded on the launch stream around each call."""
+    for k in range(warmup):
+        launch(k)
+    torch.cuda.synchronize()
+    pairs = []
+    for k in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        launch(k)
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
+
+
+def time_batch(torch, launch, reps, warmup):
+    """Average duration of back-to-back launches (one event pair around the whole batch):
+    for kernels of a few microseconds, where a per-launch event pair would dominate."""
+    for k in range(warmup):
+        launch(k)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for k in range(reps):
+        launch(k)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def cpu_baseline(torch, W, w, coord, x_dev, sample):
+    """The oracle, as it stands, on the first `sample` elements of the same shard."""
+    import numpy as np
+    import oracle
+    threads = min(16, os.cpu_count() or 1)
+    args = tuple(w.sharding_args(coord))
+    n = x_dev.numel()
+    xh = np.zeros(n, dtype=np.uint16)    # untouched pages cost nothing; only the sample is filled
+    xh[:sample] = x_dev[:sample].view(torch.int16).cpu().numpy().view(np.uint16)
+    t0 = time.perf_counter()
+    oracle.dropout(args, oracle.BF16, w.params["p"], w.seed, 0, xh, i_begin=0, i_end=sample, threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": algorithmic_bytes(w.op, w.dtype, sample) / dt / 1e9, "unit": "GB/s", "cores": threads,
+            "kind": "oracle", "seconds": dt,
+            "sample": "first %d of %d elements of the same C5 shard (scalar C++ oracle, %d std::threads)" % (sample, n, threads)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-config side measurements")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known size) to scale rocprofv3's byte counters")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (mesh ranks are emulated on it); --gpus above 1 is not supported")
+
+    import torch
+    import paper_2509_07003_amd as v
+    from paper_2509_07003_amd import workloads as W
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+
+    w, coord = W.C5, W.C5.bench_coord
+    sh = v.Sharding(*w.sharding_args(coord))
+    shape, n = v.vesrng_local_shape(sh)
+    x = W.device_activations(shape, w.input_seed, w.input_kind, w.dtype).reshape(-1)
+    y = torch.empty_like(x)
+    mask = torch.empty(n, dtype=torch.uint8, device="cuda")
+    nbytes = algorithmic_bytes(w.op, w.dtype, n)
+    state = {"offset": 0}
+
+    def step(_k=0):
+        v.vesrng_dropout(sh, v.BF16, w.params["p"], w.seed, state["offset"], x, y, mask)
+        state["offset"] = v.vesrng_advance_offset(sh, state["offset"])
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / a.steps
+    value = nbytes / (wall / a.steps) / 1e9
+
+    # Dominant (only) kernel of the step, timed with events on the launch stream.
+    avg_ms, med_ms, min_ms = time_kernel(torch, step, a.steps, 2)
+    achieved = nbytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "aligned_kernel<dropout,bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("c5_dropout_bf16"),
+                "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms,
+                "algorithmic_bytes_per_launch": nbytes}
+
+    out = {"metric": "sharded RNG fill / fused dropout GB/s per MI355X and % of HBM peak", "value": value,
+           "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u32 Philox + f32 scale, bf16 in/out, u8 mask", "data": "synthetic",
+           "config": {"workload": w.name, "rank": coord, "local_shape": shape, "elements": n,
+                      "gsamples_per_s": n / (wall / a.steps) / 1e9, "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
+           "roofline": roofline}
+
+    if a.calibrate_copy:
+        for _ in range(3):
+            y.copy_(x)   # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, W, w, coord, x, sample=n)
+
+    if not a.no_extra:
+        del x, y, mask
+        extra = {}
+        for wl, copies in ((W.C1, 256), (W.C2, 16), (W.C3, 32), (W.C4, 8), (W.C5_INTERLEAVED, 1)):
+            launch, numel, nb = make_launcher(v, W, torch, wl, wl.bench_coord, copies)
+            avg = time_batch(torch, launch, max(50, a.steps), 5)
+            extra[wl.name.split()[0] + ("i" if wl is W.C5_INTERLEAVED else "")] = {
+                "workload": wl.name, "elements": numel, "algorithmic_bytes": nb, "avg_launch_us": avg * 1e3,
+                "gb_per_s": nb / (avg * 1e-3) / 1e9, "gsamples_per_s": numel / (avg * 1e-3) / 1e9,
+                "pct_hbm_peak": 100 * nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_cycled": copies,
+                "note": "back-to-back launches incl. host call overhead; buffers cycled to exceed the last-level cache"}
+        out["per_config"] = extra
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
