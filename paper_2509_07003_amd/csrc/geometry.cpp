@@ -226,7 +226,8 @@ RunShape run_shape(const Geometry& g) {
 }
 
 bool fits_32bit(const RunShape& rs, uint64_t units_per_run) {
-  const uint64_t lim = 1ull << 31;
+  // 2^30 rather than 2^31: the kernels also form small signed differences of these values.
+  const uint64_t lim = 1ull << 30;
   if (rs.run_len >= lim || units_per_run >= lim) return false;
   if (rs.n_runs >= lim || rs.n_runs * units_per_run >= lim) return false;
   // Local flat indices are formed as run * run_len + k in the index type.

@@ -37,6 +37,12 @@ constexpr int kThreads = 256;
 constexpr int kF32 = 0, kBF16 = 1;
 
 // ---- generator ---------------------------------------------------------------
+// a ^ b ^ c in one instruction (v_bitop3_b32, truth table 0x96); the compiler emits two
+// v_xor_b32 for the plain expression, and the XORs are half of Philox's instructions.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 on counter (lo32 b, hi32 b, 0, 0), key (k0, k1).
 __device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k1, uint32_t (&w)[4]) {
   uint32_t c0 = static_cast<uint32_t>(b), c1 = static_cast<uint32_t>(b >> 32), c2 = 0u, c3 = 0u;
@@ -44,8 +50,8 @@ __device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k
   for (int round = 0; round < 10; ++round) {
     const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
     const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
     c1 = static_cast<uint32_t>(p1);
     c3 = static_cast<uint32_t>(p0);
     c0 = n0;
@@ -124,18 +130,41 @@ struct UnitOf {
   static constexpr int kElems = 4 * kBlocks;
 };
 
-template <int OP, int DT, typename IT>
+// Position (stream position of the first element) of work unit `w`.  NOUT is the number
+// of run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
+// shards (a contiguous slice; one strided axis of runs) then need no loop and no loads
+// that depend on a loop counter.
+template <int NOUT, typename IT>
+__device__ __forceinline__ void locate(const PlanT<IT>& plan, IT w, IT& run, IT& unit, uint64_t& run_pos) {
+  if constexpr (NOUT == 0) {
+    run = 0;
+    unit = w;
+    run_pos = plan.pos0;
+  } else {
+    run = plan.units_div.div(w);
+    unit = w - run * plan.units_per_run;
+    if constexpr (NOUT == 1)
+      run_pos = plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
+    else
+      run_pos = plan.pos0 + run_offset(plan, run);
+  }
+}
+
+template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
   constexpr int NB = UnitOf<OP, DT>::kBlocks;
   constexpr int V = UnitOf<OP, DT>::kElems;
-  const uint64_t w64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  if (w64 >= plan.total_units) return;
+  // Threads past the end compute unit 0 again and skip the stores: no early exit, so all
+  // kernel arguments are fetched in one batch at the top.
+  const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  const bool live = t64 < plan.total_units;
+  const uint64_t w64 = live ? t64 : 0;
   const IT w = static_cast<IT>(w64);
-  const IT run = plan.units_div.div(w);
-  const IT unit = w - run * plan.units_per_run;
-  const uint64_t pos = plan.pos0 + run_offset(plan, run) + static_cast<uint64_t>(unit) * V;
-  const uint64_t block0 = pos >> 2;
+  IT run, unit;
+  uint64_t run_pos;
+  locate<NOUT>(plan, w, run, unit, run_pos);
+  const uint64_t block0 = (run_pos + static_cast<uint64_t>(unit) * V) >> 2;
 
   // Dropout: issue the load before the generator so that it overlaps the ALU work.
   u32x4 xv = {0u, 0u, 0u, 0u};
@@ -144,6 +173,13 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   uint32_t d[NB][4];
 #pragma unroll
   for (int b = 0; b < NB; ++b) philox_block(block0 + b, prm.key0, prm.key1, d[b]);
+  // Keep the generator (and the argument loads it needs) ahead of the bounds branch: without
+  // this the compiler sinks everything below the branch and fetches the arguments in two
+  // dependent rounds.
+#pragma unroll
+  for (int b = 0; b < NB; ++b) asm volatile("" : "+v"(d[b][0]), "+v"(d[b][1]), "+v"(d[b][2]), "+v"(d[b][3]));
+  if constexpr (OP == kOpDropout) asm volatile("" : "+v"(xv));
+  if (!live) return;
 
   if constexpr (OP == kOpRaw) {
     const u32x4 v = {d[0][0], d[0][1], d[0][2], d[0][3]};
@@ -222,29 +258,43 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 }
 
 // ---- ragged / general kernels ----------------------------------------------------
-template <int OP, int DT, typename IT>
+template <typename IT>
+struct SignedOf;
+template <>
+struct SignedOf<uint32_t> {
+  using type = int32_t;
+};
+template <>
+struct SignedOf<uint64_t> {
+  using type = int64_t;
+};
+
+template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
-  const uint64_t w64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  if (w64 >= plan.total_units) return;
-  const IT w = static_cast<IT>(w64);
-  const IT run = plan.units_div.div(w);
-  const IT bi = w - run * plan.units_per_run;          // block number inside the run
-  const uint64_t run_pos = plan.pos0 + run_offset(plan, run);
+  using ST = typename SignedOf<IT>::type;
+  const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  const bool in_range = t64 < plan.total_units;
+  const IT w = in_range ? static_cast<IT>(t64) : 0;
+  IT run, bi;  // bi: block number inside the run
+  uint64_t run_pos;
+  locate<NOUT>(plan, w, run, bi, run_pos);
   const uint32_t phase = static_cast<uint32_t>(run_pos) & 3u;
+  // Elements of the run from this block's lane 0 onwards (lane 0 may lie before the run).
+  // Not positive only when runs differ in phase and units_per_run is the upper bound.
+  const ST remaining = static_cast<ST>(phase + plan.run_len) - static_cast<ST>(4 * bi);
+  const bool live = in_range && remaining > 0;
   // Lanes [first, last) of this block belong to the run.
-  const uint64_t before = static_cast<uint64_t>(bi) * 4u;  // block start relative to the run's first block
-  const uint64_t run_end = static_cast<uint64_t>(phase) + plan.run_len;
-  if (before >= run_end) return;  // only when runs differ in phase and units_per_run is the upper bound
   const uint32_t first = (bi == 0) ? phase : 0u;
-  const uint64_t remaining = run_end - before;
-  const uint32_t last = remaining < 4u ? static_cast<uint32_t>(remaining) : 4u;
-  // Local flat index of lane 0 (may lie before the run for the first block: only valid lanes are touched).
-  const int64_t li0 = static_cast<int64_t>(static_cast<uint64_t>(run) * plan.run_len + before) -
-                      static_cast<int64_t>(phase);
+  const uint32_t last = remaining < 4 ? static_cast<uint32_t>(remaining) : 4u;
+  // Local flat index of lane 0 (negative for the very first block of a shard with phase > 0:
+  // only valid lanes are touched).
+  const int64_t li0 = static_cast<int64_t>(static_cast<ST>(run * plan.run_len + 4 * bi) - static_cast<ST>(phase));
 
   uint32_t d[4];
   philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
+  asm volatile("" : "+v"(d[0]), "+v"(d[1]), "+v"(d[2]), "+v"(d[3]));  // see aligned_kernel
+  if (!live) return;
 
   const bool full = (first == 0u) && (last == 4u);
   if constexpr (OP == kOpRaw) {
@@ -331,19 +381,29 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
 }
 
 // ---- dispatch --------------------------------------------------------------------
-template <int OP, int DT, typename IT>
-hipError_t launch_typed(bool aligned, const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run,
-                        const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
-  const PlanT<IT> plan = make_plan<IT>(g, rs, offset, units_per_run);
+template <int OP, int DT, typename IT, int NOUT>
+hipError_t launch_nout(bool aligned, const PlanT<IT>& plan, const OpParams& prm, const void* x, void* out,
+                       uint8_t* mask, hipStream_t stream) {
   const uint64_t blocks = (plan.total_units + kThreads - 1) / kThreads;
   if (blocks == 0) return hipSuccess;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
   if (aligned)
-    hipLaunchKernelGGL((aligned_kernel<OP, DT, IT>), grid, block, 0, stream, plan, prm, x, out, mask);
+    hipLaunchKernelGGL((aligned_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
   else
-    hipLaunchKernelGGL((ragged_kernel<OP, DT, IT>), grid, block, 0, stream, plan, prm, x, out, mask);
+    hipLaunchKernelGGL((ragged_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
   return hipGetLastError();
+}
+
+template <int OP, int DT, typename IT>
+hipError_t launch_typed(bool aligned, const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run,
+                        const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
+  const PlanT<IT> plan = make_plan<IT>(g, rs, offset, units_per_run);
+  switch (plan.n_outer) {
+    case 0: return launch_nout<OP, DT, IT, 0>(aligned, plan, prm, x, out, mask, stream);
+    case 1: return launch_nout<OP, DT, IT, 1>(aligned, plan, prm, x, out, mask, stream);
+    default: return launch_nout<OP, DT, IT, 2>(aligned, plan, prm, x, out, mask, stream);
+  }
 }
 
 template <int OP, int DT>
