@@ -4,17 +4,23 @@
 // Work decomposition.  Algorithm 1 walks local elements one by one.  Here a
 // thread owns one generator block (4 consecutive stream positions, hence 4
 // consecutive global elements) or two of them, so that one Philox call feeds
-// four outputs that stay in registers and leave as one 128-bit store.
+// four outputs that stay in registers.
 //
 //  * aligned kernels: every run of the shard starts on a block boundary and its
 //    length is a multiple of the unit (4 or 8 elements); unit w covers local
 //    elements [w*V, (w+1)*V) and all accesses are 16-byte vectors.
-//  * ragged kernels: any run start / length; a thread still owns one global
-//    block and stores only the lanes that fall inside the run (e.g. a column
-//    shard whose first column is 1366).  They also serve as the general path.
+//  * tiled kernels: any run start / length (e.g. a column shard whose first
+//    column is 1366).  A workgroup owns a 16-byte aligned tile of the LOCAL
+//    tensor; its threads first own the GLOBAL blocks that intersect the tile and
+//    scatter their values into LDS at local positions, then each thread takes an
+//    aligned unit back out of LDS and stores it.  One block still feeds four
+//    outputs, and every global access is an aligned 128-bit vector: 16-byte
+//    stores that are only 4- or 8-byte aligned run at 4.9 instead of 6.8 TB/s.
+//  * ragged kernels: the element-wise general path (runs shorter than 16
+//    elements, innermost global stride other than 1).
 //
-// The launch is one-shot (one unit per thread): on MI355X this sustained a higher
-// store rate than a grid-stride loop over the same bytes.
+// Launches are one-shot (one unit per thread): on MI355X this sustained a higher
+// rate than grid-stride loops or several units per thread.
 #include <hip/hip_runtime.h>
 
 #include "launch.hpp"
@@ -28,13 +34,28 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-// 16 bytes that are only 4-byte aligned: row starts of a ragged fp32 shard.
+
+// 16 / 8 bytes that are only 4-byte aligned: whole blocks inside a ragged run.
 struct __attribute__((packed, aligned(4))) U32x4Unaligned {
   uint32_t a, b, c, d;
+};
+struct __attribute__((packed, aligned(4))) U32x2Unaligned {
+  uint32_t a, b;
 };
 
 constexpr int kThreads = 256;
 constexpr int kF32 = 0, kBF16 = 1;
+
+template <typename IT>
+struct SignedOf;
+template <>
+struct SignedOf<uint32_t> {
+  using type = int32_t;
+};
+template <>
+struct SignedOf<uint64_t> {
+  using type = int64_t;
+};
 
 // ---- generator ---------------------------------------------------------------
 // a ^ b ^ c in one instruction (v_bitop3_b32, truth table 0x96); the compiler emits two
@@ -83,9 +104,9 @@ __device__ __forceinline__ float uniform_value(uint32_t x, const OpParams& prm) 
   return r >= prm.high ? prm.top_f32 : r;
 }
 
-// bfloat16 bits of one uniform (upper guard applied after rounding).
-__device__ __forceinline__ uint32_t uniform_bf16_pair(uint32_t xa, uint32_t xb, const OpParams& prm) {
-  uint32_t pair = pack_bf16(uniform_value(xa, prm), uniform_value(xb, prm));
+// Two fp32 uniforms rounded to a bfloat16 pair (upper guard applied after rounding).
+__device__ __forceinline__ uint32_t uniform_bf16_pack(float a, float b, const OpParams& prm) {
+  uint32_t pair = pack_bf16(a, b);
   if (bf16_lo(pair) >= prm.high) pair = (pair & 0xFFFF0000u) | prm.top_bf16;
   if (bf16_hi(pair) >= prm.high) pair = (pair & 0x0000FFFFu) | (prm.top_bf16 << 16);
   return pair;
@@ -122,34 +143,172 @@ __device__ __forceinline__ int64_t randint_value(uint32_t x, const OpParams& prm
   return prm.base + static_cast<int64_t>(rem);
 }
 
-// ---- aligned kernels -----------------------------------------------------------
-// OP: OpKind.  DT: output dtype.  One thread = one unit of V elements.
+// The per-element value of a whole generator block, as 32-bit patterns: fp32 bits for
+// uniform and normal (whatever the output dtype), the raw draws for the operators whose
+// conversion needs more than the draw (dropout needs x, randint widens to 64 bits).
+template <int OP>
+__device__ __forceinline__ void convert_block(const uint32_t (&d)[4], const OpParams& prm, uint32_t (&v)[4]) {
+  if constexpr (OP == kOpUniform) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(uniform_value(d[e], prm));
+  } else if constexpr (OP == kOpNormal) {
+    float n[4];
+    normal_pair(d[0], d[1], prm, n[0], n[1]);
+    normal_pair(d[2], d[3], prm, n[2], n[3]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(n[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = d[e];
+  }
+}
+
+// OP: OpKind.  DT: output dtype.  A unit is what one thread stores: V elements.
 template <int OP, int DT>
 struct UnitOf {
   static constexpr int kBlocks = (OP != kOpRaw && OP != kOpRandint && DT == kBF16) ? 2 : 1;
   static constexpr int kElems = 4 * kBlocks;
 };
 
-// Position (stream position of the first element) of work unit `w`.  NOUT is the number
-// of run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
-// shards (a contiguous slice; one strided axis of runs) then need no loop and no loads
-// that depend on a loop counter.
+// Writes unit number `u` of the local tensor (elements [u*V, (u+1)*V)) from the V values
+// made by convert_block; dropout also consumes the 16 bytes of x loaded for the unit.
+template <int OP, int DT>
+__device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kElems], const OpParams& prm,
+                                          u32x4 xv, uint64_t u, void* out, uint8_t* mask) {
+  constexpr int NB = UnitOf<OP, DT>::kBlocks;
+  if constexpr (OP == kOpRandint) {
+    int64_t r[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = randint_value(v[e], prm);
+    const u32x4 lo = {static_cast<uint32_t>(r[0]), static_cast<uint32_t>(static_cast<uint64_t>(r[0]) >> 32),
+                      static_cast<uint32_t>(r[1]), static_cast<uint32_t>(static_cast<uint64_t>(r[1]) >> 32)};
+    const u32x4 hi = {static_cast<uint32_t>(r[2]), static_cast<uint32_t>(static_cast<uint64_t>(r[2]) >> 32),
+                      static_cast<uint32_t>(r[3]), static_cast<uint32_t>(static_cast<uint64_t>(r[3]) >> 32)};
+    __builtin_nontemporal_store(lo, static_cast<u32x4*>(out) + 2 * u);
+    __builtin_nontemporal_store(hi, static_cast<u32x4*>(out) + 2 * u + 1);
+  } else if constexpr (OP == kOpDropout) {
+    u32x4 y;
+    if constexpr (DT == kF32) {
+      uint32_t m = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool keep = keep_of(v[e], prm);
+        const float prod = __fmul_rn(__uint_as_float(xv[e]), prm.scale);
+        y[e] = keep ? __float_as_uint(prod) : 0u;
+        m |= (keep ? 1u : 0u) << (8 * e);
+      }
+      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + u);
+      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<uint32_t*>(mask) + u);
+    } else {
+      u32x2 m = {0u, 0u};
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {  // two packed pairs per block
+          const uint32_t pair = xv[2 * b + h];
+          const bool k0 = keep_of(v[4 * b + 2 * h], prm), k1 = keep_of(v[4 * b + 2 * h + 1], prm);
+          const float p0 = __fmul_rn(bf16_lo(pair), prm.scale);
+          const float p1 = __fmul_rn(bf16_hi(pair), prm.scale);
+          // Select before rounding: a dropped element becomes +0 whatever x held.
+          y[2 * b + h] = pack_bf16(k0 ? p0 : 0.0f, k1 ? p1 : 0.0f);
+          m[b] |= ((k0 ? 1u : 0u) | (k1 ? 0x100u : 0u)) << (16 * h);
+        }
+      }
+      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + u);
+      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<u32x2*>(mask) + u);
+    }
+  } else {
+    u32x4 o;
+    if constexpr (OP == kOpRaw || DT == kF32) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = v[e];
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(v[2 * q]), b = __uint_as_float(v[2 * q + 1]);
+        o[q] = (OP == kOpUniform) ? uniform_bf16_pack(a, b, prm) : pack_bf16(a, b);
+      }
+    }
+    __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + u);
+  }
+}
+
+// Writes ONE local element `i` from its convert_block value (edges of ragged shards).
+template <int OP, int DT>
+__device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, const void* xin, int64_t i, void* out,
+                                             uint8_t* mask) {
+  if constexpr (OP == kOpRaw) {
+    static_cast<uint32_t*>(out)[i] = v;
+  } else if constexpr (OP == kOpRandint) {
+    static_cast<int64_t*>(out)[i] = randint_value(v, prm);
+  } else if constexpr (OP == kOpDropout) {
+    const bool keep = keep_of(v, prm);
+    if constexpr (DT == kF32) {
+      const float x = static_cast<const float*>(xin)[i];
+      static_cast<float*>(out)[i] = keep ? __fmul_rn(x, prm.scale) : 0.0f;
+    } else {
+      const uint32_t x = static_cast<const uint16_t*>(xin)[i];
+      const float prod = __fmul_rn(__uint_as_float(x << 16), prm.scale);
+      static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pack_bf16(keep ? prod : 0.0f, 0.0f));
+    }
+    if (mask) mask[i] = keep ? 1 : 0;
+  } else if constexpr (DT == kF32) {
+    static_cast<uint32_t*>(out)[i] = v;
+  } else {
+    const float a = __uint_as_float(v);
+    const uint32_t pair = (OP == kOpUniform) ? uniform_bf16_pack(a, a, prm) : pack_bf16(a, a);
+    static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pair);
+  }
+}
+
+// ---- locating work ---------------------------------------------------------------
+// Stream position of the first element of run `run`.  NOUT is the number of
+// run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
+// shards (a contiguous slice; one strided axis of runs) need no loop and no argument
+// loads that depend on a loop counter.
+template <int NOUT, typename IT>
+__device__ __forceinline__ uint64_t run_position(const PlanT<IT>& plan, IT run) {
+  if constexpr (NOUT == 0) return plan.pos0;
+  else if constexpr (NOUT == 1) return plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
+  else return plan.pos0 + run_offset(plan, run);
+}
+
+// Work unit w -> (run, unit inside the run, stream position of the run).
 template <int NOUT, typename IT>
 __device__ __forceinline__ void locate(const PlanT<IT>& plan, IT w, IT& run, IT& unit, uint64_t& run_pos) {
   if constexpr (NOUT == 0) {
     run = 0;
     unit = w;
-    run_pos = plan.pos0;
   } else {
     run = plan.units_div.div(w);
     unit = w - run * plan.units_per_run;
-    if constexpr (NOUT == 1)
-      run_pos = plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
-    else
-      run_pos = plan.pos0 + run_offset(plan, run);
   }
+  run_pos = run_position<NOUT>(plan, run);
 }
 
+// The part of global block `bi` of a run that belongs to the run.
+template <typename IT>
+struct BlockSpan {
+  uint32_t first, last;  // lanes [first, last) are inside the run (last = 0: none)
+  typename SignedOf<IT>::type li0;  // local flat index of lane 0 (may lie before the run: only valid lanes are used)
+  bool any;
+};
+template <typename IT>
+__device__ __forceinline__ BlockSpan<IT> block_span(const PlanT<IT>& plan, IT run, IT bi, uint64_t run_pos) {
+  using ST = typename SignedOf<IT>::type;
+  const uint32_t phase = static_cast<uint32_t>(run_pos) & 3u;
+  // Elements of the run from this block's lane 0 onwards.  Not positive only when runs differ
+  // in phase and units_per_run is the upper bound over phases.
+  const ST remaining = static_cast<ST>(phase + plan.run_len) - static_cast<ST>(4 * bi);
+  BlockSpan<IT> s;
+  s.any = remaining > 0;
+  s.first = (bi == 0) ? phase : 0u;
+  s.last = remaining < 4 ? static_cast<uint32_t>(remaining > 0 ? remaining : 0) : 4u;
+  s.li0 = static_cast<ST>(run * plan.run_len + 4 * bi) - static_cast<ST>(phase);
+  return s;
+}
+
+// ---- aligned kernels -----------------------------------------------------------
 template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
@@ -181,229 +340,209 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   if constexpr (OP == kOpDropout) asm volatile("" : "+v"(xv));
   if (!live) return;
 
-  if constexpr (OP == kOpRaw) {
-    const u32x4 v = {d[0][0], d[0][1], d[0][2], d[0][3]};
-    __builtin_nontemporal_store(v, static_cast<u32x4*>(out) + w64);
-  } else if constexpr (OP == kOpRandint) {
-    int64_t r[4];
+  uint32_t v[V];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = randint_value(d[0][e], prm);
-    u32x4 lo = {static_cast<uint32_t>(r[0]), static_cast<uint32_t>(static_cast<uint64_t>(r[0]) >> 32),
-                static_cast<uint32_t>(r[1]), static_cast<uint32_t>(static_cast<uint64_t>(r[1]) >> 32)};
-    u32x4 hi = {static_cast<uint32_t>(r[2]), static_cast<uint32_t>(static_cast<uint64_t>(r[2]) >> 32),
-                static_cast<uint32_t>(r[3]), static_cast<uint32_t>(static_cast<uint64_t>(r[3]) >> 32)};
-    __builtin_nontemporal_store(lo, static_cast<u32x4*>(out) + 2 * w64);
-    __builtin_nontemporal_store(hi, static_cast<u32x4*>(out) + 2 * w64 + 1);
-  } else if constexpr (OP == kOpUniform) {
-    u32x4 v;
-    if constexpr (DT == kF32) {
+  for (int b = 0; b < NB; ++b) {
+    uint32_t vb[4];
+    convert_block<OP>(d[b], prm, vb);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(uniform_value(d[0][e], prm));
-    } else {
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        v[2 * b] = uniform_bf16_pair(d[b][0], d[b][1], prm);
-        v[2 * b + 1] = uniform_bf16_pair(d[b][2], d[b][3], prm);
-      }
-    }
-    __builtin_nontemporal_store(v, static_cast<u32x4*>(out) + w64);
-  } else if constexpr (OP == kOpNormal) {
-    u32x4 v;
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      float n[4];
-      normal_pair(d[b][0], d[b][1], prm, n[0], n[1]);
-      normal_pair(d[b][2], d[b][3], prm, n[2], n[3]);
-      if constexpr (DT == kF32) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(n[e]);
-      } else {
-        v[2 * b] = pack_bf16(n[0], n[1]);
-        v[2 * b + 1] = pack_bf16(n[2], n[3]);
-      }
-    }
-    __builtin_nontemporal_store(v, static_cast<u32x4*>(out) + w64);
-  } else if constexpr (OP == kOpDropout) {
-    u32x4 y;
-    if constexpr (DT == kF32) {
-      uint32_t m = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const bool keep = keep_of(d[0][e], prm);
-        const float prod = __fmul_rn(__uint_as_float(xv[e]), prm.scale);
-        y[e] = keep ? __float_as_uint(prod) : 0u;
-        m |= (keep ? 1u : 0u) << (8 * e);
-      }
-      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + w64);
-      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<uint32_t*>(mask) + w64);
-    } else {
-      u32x2 m = {0u, 0u};
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {  // two packed pairs per block
-          const uint32_t pair = xv[2 * b + h];
-          const bool k0 = keep_of(d[b][2 * h], prm), k1 = keep_of(d[b][2 * h + 1], prm);
-          const float p0 = __fmul_rn(bf16_lo(pair), prm.scale);
-          const float p1 = __fmul_rn(bf16_hi(pair), prm.scale);
-          // Select before rounding: a dropped element becomes +0 whatever x held.
-          y[2 * b + h] = pack_bf16(k0 ? p0 : 0.0f, k1 ? p1 : 0.0f);
-          m[b] |= ((k0 ? 1u : 0u) | (k1 ? 0x100u : 0u)) << (16 * h);
-        }
-      }
-      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + w64);
-      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<u32x2*>(mask) + w64);
-    }
+    for (int e = 0; e < 4; ++e) v[4 * b + e] = vb[e];
   }
+  emit_unit<OP, DT>(v, prm, xv, w64, out, mask);
 }
 
-// ---- ragged / general kernels ----------------------------------------------------
+// ---- tiled kernels ---------------------------------------------------------------
+// plan.units_per_run counts the generator blocks a run can touch (as for the ragged
+// kernel).  `tile_units` aligned units of the local tensor form one workgroup's tile;
+// run_len_div divides by the run length.
 template <typename IT>
-struct SignedOf;
-template <>
-struct SignedOf<uint32_t> {
-  using type = int32_t;
-};
-template <>
-struct SignedOf<uint64_t> {
-  using type = int64_t;
+struct TileArgs {
+  typename PlanT<IT>::Div run_len_div;
+  IT tile_units;
+  uint64_t local_numel;
 };
 
 template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
-ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
+tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, const void* xin, void* out,
+             uint8_t* mask) {
   using ST = typename SignedOf<IT>::type;
+  constexpr int V = UnitOf<OP, DT>::kElems;
+  // One 32-bit value per local element of the tile, plus a slot that swallows the lanes of
+  // edge blocks that fall outside the tile or the run (cheaper than predicated LDS writes).
+  constexpr int kDummy = kThreads * V;
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kThreads * V + 4];
+
+  const uint64_t tile_elems = static_cast<uint64_t>(ta.tile_units) * V;
+  const uint64_t i0 = static_cast<uint64_t>(blockIdx.x) * tile_elems;  // first local element of the tile
+  const uint64_t i1 = (i0 + tile_elems < ta.local_numel) ? i0 + tile_elems : ta.local_numel;
+  const int32_t lim = static_cast<int32_t>(i1 - i0);
+
+  // Generator blocks that intersect [i0, i1): flattened (run, block) numbers wa .. wa + count - 1.
+  auto block_of = [&](uint64_t i) -> IT {
+    const IT ii = static_cast<IT>(i);
+    const IT run = ta.run_len_div.div(ii);
+    const IT c = ii - run * plan.run_len;
+    const uint32_t phase = static_cast<uint32_t>(run_position<NOUT>(plan, run)) & 3u;
+    return run * plan.units_per_run + ((c + phase) >> 2);
+  };
+  const IT wa = block_of(i0);
+  const IT count = block_of(i1 - 1) - wa + 1;
+
+  // Stage A: one block per thread (one pass for 4-byte units, two for bfloat16 units).
+  // Everything is kept in tile coordinates (local index minus i0), which fit 32 bits.
+  for (IT k = threadIdx.x; k < count; k += kThreads) {
+    IT run, bi;
+    uint64_t run_pos;
+    locate<NOUT>(plan, static_cast<IT>(wa + k), run, bi, run_pos);
+    uint32_t d[4], v[4];
+    philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
+    convert_block<OP>(d, prm, v);
+    // The run occupies tile positions [run_lo, run_lo + run_len); lane e of this block sits at
+    // rel + e.  A lane is written when it is inside both the run and the tile; the other lanes
+    // of edge blocks (and the dead slots of runs that differ in phase) go to the dummy slot.
+    const int32_t run_lo = static_cast<int32_t>(static_cast<ST>(run * plan.run_len) - static_cast<ST>(i0));
+    const int32_t rel =
+        run_lo + static_cast<int32_t>(4 * bi) - static_cast<int32_t>(static_cast<uint32_t>(run_pos) & 3u);
+    const int32_t lo = max(run_lo, 0);
+    const int32_t hi = min(run_lo + static_cast<int32_t>(plan.run_len), lim);
+    const uint32_t width = static_cast<uint32_t>(hi - lo);  // hi > lo: the run intersects the tile
+    const uint32_t base = static_cast<uint32_t>(rel - lo);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[(base + e < width) ? rel + e : kDummy] = v[e];
+  }
+  __syncthreads();
+
+  // Stage B: one aligned unit per thread out of LDS.
+  const uint64_t u = static_cast<uint64_t>(blockIdx.x) * ta.tile_units + threadIdx.x;
+  const uint64_t e0 = u * V;
+  if (threadIdx.x >= ta.tile_units || e0 >= i1) return;
+  if (e0 + V <= i1) {
+    uint32_t v[V];
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) {
+      const u32x4 t = *reinterpret_cast<const u32x4*>(&tile[threadIdx.x * V + 4 * q]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[4 * q + e] = t[e];
+    }
+    u32x4 xv = {0u, 0u, 0u, 0u};
+    if constexpr (OP == kOpDropout) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
+    emit_unit<OP, DT>(v, prm, xv, u, out, mask);
+  } else {
+    // The last unit of a shard whose size is not a multiple of the unit.
+    for (uint64_t i = e0; i < i1; ++i)
+      emit_element<OP, DT>(tile[i - i0], prm, xin, static_cast<int64_t>(i), out, mask);
+  }
+}
+
+// ---- ragged / general kernels ----------------------------------------------------
+template <int OP, int DT, typename IT, int NOUT>
+__global__ void __launch_bounds__(kThreads)
+ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
   const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   const bool in_range = t64 < plan.total_units;
   const IT w = in_range ? static_cast<IT>(t64) : 0;
   IT run, bi;  // bi: block number inside the run
   uint64_t run_pos;
   locate<NOUT>(plan, w, run, bi, run_pos);
-  const uint32_t phase = static_cast<uint32_t>(run_pos) & 3u;
-  // Elements of the run from this block's lane 0 onwards (lane 0 may lie before the run).
-  // Not positive only when runs differ in phase and units_per_run is the upper bound.
-  const ST remaining = static_cast<ST>(phase + plan.run_len) - static_cast<ST>(4 * bi);
-  const bool live = in_range && remaining > 0;
-  // Lanes [first, last) of this block belong to the run.
-  const uint32_t first = (bi == 0) ? phase : 0u;
-  const uint32_t last = remaining < 4 ? static_cast<uint32_t>(remaining) : 4u;
-  // Local flat index of lane 0 (negative for the very first block of a shard with phase > 0:
-  // only valid lanes are touched).
-  const int64_t li0 = static_cast<int64_t>(static_cast<ST>(run * plan.run_len + 4 * bi) - static_cast<ST>(phase));
+  const BlockSpan<IT> s = block_span(plan, run, bi, run_pos);
 
   uint32_t d[4];
   philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
   asm volatile("" : "+v"(d[0]), "+v"(d[1]), "+v"(d[2]), "+v"(d[3]));  // see aligned_kernel
-  if (!live) return;
+  if (!in_range || !s.any) return;
 
-  const bool full = (first == 0u) && (last == 4u);
-  if constexpr (OP == kOpRaw) {
-    uint32_t* o = static_cast<uint32_t*>(out) + li0;
-    if (full) {
-      *reinterpret_cast<U32x4Unaligned*>(o) = U32x4Unaligned{d[0], d[1], d[2], d[3]};
-    } else {
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) o[e] = d[e];
-    }
-  } else if constexpr (OP == kOpRandint) {
-    int64_t* o = static_cast<int64_t*>(out) + li0;
-#pragma unroll
-    for (uint32_t e = 0; e < 4; ++e)
-      if (e >= first && e < last) o[e] = randint_value(d[e], prm);
-  } else if constexpr (OP == kOpUniform || OP == kOpNormal) {
-    float v[4];
-    if constexpr (OP == kOpUniform) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = uniform_value(d[e], prm);
-    } else {
-      normal_pair(d[0], d[1], prm, v[0], v[1]);
-      normal_pair(d[2], d[3], prm, v[2], v[3]);
-    }
-    if constexpr (DT == kF32) {
-      float* o = static_cast<float*>(out) + li0;
-      if (full) {
-        *reinterpret_cast<U32x4Unaligned*>(o) = U32x4Unaligned{__float_as_uint(v[0]), __float_as_uint(v[1]),
-                                                               __float_as_uint(v[2]), __float_as_uint(v[3])};
-      } else {
-#pragma unroll
-        for (uint32_t e = 0; e < 4; ++e)
-          if (e >= first && e < last) o[e] = v[e];
+  uint32_t v[4];
+  convert_block<OP>(d, prm, v);
+  const int64_t li0 = static_cast<int64_t>(s.li0);
+  // Whole blocks of the fills leave as one store that is only element-aligned.
+  if constexpr (OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) {
+    if (s.first == 0u && s.last == 4u) {
+      if constexpr (OP == kOpRaw || DT == kF32) {
+        *reinterpret_cast<U32x4Unaligned*>(static_cast<uint32_t*>(out) + li0) = U32x4Unaligned{v[0], v[1], v[2], v[3]};
+        return;
+      } else if ((li0 & 1) == 0) {
+        const float a = __uint_as_float(v[0]), b = __uint_as_float(v[1]);
+        const float c = __uint_as_float(v[2]), e = __uint_as_float(v[3]);
+        const uint32_t p01 = (OP == kOpUniform) ? uniform_bf16_pack(a, b, prm) : pack_bf16(a, b);
+        const uint32_t p23 = (OP == kOpUniform) ? uniform_bf16_pack(c, e, prm) : pack_bf16(c, e);
+        *reinterpret_cast<U32x2Unaligned*>(static_cast<uint16_t*>(out) + li0) = U32x2Unaligned{p01, p23};
+        return;
       }
-    } else {
-      uint32_t p01, p23;
-      if constexpr (OP == kOpUniform) {
-        p01 = uniform_bf16_pair(d[0], d[1], prm);
-        p23 = uniform_bf16_pair(d[2], d[3], prm);
-      } else {
-        p01 = pack_bf16(v[0], v[1]);
-        p23 = pack_bf16(v[2], v[3]);
-      }
-      const uint16_t h[4] = {static_cast<uint16_t>(p01), static_cast<uint16_t>(p01 >> 16),
-                             static_cast<uint16_t>(p23), static_cast<uint16_t>(p23 >> 16)};
-      uint16_t* o = static_cast<uint16_t*>(out) + li0;
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) o[e] = h[e];
-    }
-  } else if constexpr (OP == kOpDropout) {
-    if constexpr (DT == kF32) {
-      const float* xi = static_cast<const float*>(xin) + li0;
-      float* o = static_cast<float*>(out) + li0;
-      float xv[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) xv[e] = xi[e];
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) {
-          const bool keep = keep_of(d[e], prm);
-          o[e] = keep ? __fmul_rn(xv[e], prm.scale) : 0.0f;
-          if (mask) mask[li0 + e] = keep ? 1 : 0;
-        }
-    } else {
-      const uint16_t* xi = static_cast<const uint16_t*>(xin) + li0;
-      uint16_t* o = static_cast<uint16_t*>(out) + li0;
-      uint16_t xv[4] = {0, 0, 0, 0};
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) xv[e] = xi[e];
-#pragma unroll
-      for (uint32_t e = 0; e < 4; ++e)
-        if (e >= first && e < last) {
-          const bool keep = keep_of(d[e], prm);
-          const float prod = __fmul_rn(__uint_as_float(static_cast<uint32_t>(xv[e]) << 16), prm.scale);
-          o[e] = static_cast<uint16_t>(pack_bf16(keep ? prod : 0.0f, 0.0f));
-          if (mask) mask[li0 + e] = keep ? 1 : 0;
-        }
     }
   }
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (static_cast<uint32_t>(e) >= s.first && static_cast<uint32_t>(e) < s.last)
+      emit_element<OP, DT>(v[e], prm, xin, li0 + e, out, mask);
 }
 
 // ---- dispatch --------------------------------------------------------------------
+enum Flavour { kAligned, kTiled, kRagged };
+// Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
+// through LDS doubles the rate of bf16 dropout (4.7 vs 2.4 TB/s) and helps the raw fill
+// (4.7 vs 4.1), but the uniform and normal fills spend too much arithmetic per element to
+// gain from it (4.0 vs 4.2 TB/s), so they keep the ragged kernel.
+template <int OP>
+constexpr bool kTileable = (OP == kOpRaw || OP == kOpRandint || OP == kOpDropout);
+
 template <int OP, int DT, typename IT, int NOUT>
-hipError_t launch_nout(bool aligned, const PlanT<IT>& plan, const OpParams& prm, const void* x, void* out,
-                       uint8_t* mask, hipStream_t stream) {
-  const uint64_t blocks = (plan.total_units + kThreads - 1) / kThreads;
+hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
+                       const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
+  constexpr uint64_t V = UnitOf<OP, DT>::kElems;
+  uint64_t blocks;
+  if (flavour == kTiled)
+    blocks = (local_numel + tile_units * V - 1) / (tile_units * V);
+  else
+    blocks = (plan.total_units + kThreads - 1) / kThreads;
   if (blocks == 0) return hipSuccess;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
-  if (aligned)
-    hipLaunchKernelGGL((aligned_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
-  else
-    hipLaunchKernelGGL((ragged_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
+  switch (flavour) {
+    case kAligned:
+      hipLaunchKernelGGL((aligned_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
+      break;
+    case kTiled:
+      if constexpr (kTileable<OP>)
+        hipLaunchKernelGGL((tiled_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm,
+                           (TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}),
+                           x, out, mask);
+      else
+        return hipErrorInvalidValue;
+      break;
+    case kRagged:
+      hipLaunchKernelGGL((ragged_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
+      break;
+  }
   return hipGetLastError();
 }
 
 template <int OP, int DT, typename IT>
-hipError_t launch_typed(bool aligned, const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run,
-                        const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
+hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, uint64_t offset,
+                        uint64_t units_per_run, uint64_t tile_units, const OpParams& prm, const void* x, void* out,
+                        uint8_t* mask, hipStream_t stream) {
   const PlanT<IT> plan = make_plan<IT>(g, rs, offset, units_per_run);
+  const uint64_t n = static_cast<uint64_t>(g.local_numel);
   switch (plan.n_outer) {
-    case 0: return launch_nout<OP, DT, IT, 0>(aligned, plan, prm, x, out, mask, stream);
-    case 1: return launch_nout<OP, DT, IT, 1>(aligned, plan, prm, x, out, mask, stream);
-    default: return launch_nout<OP, DT, IT, 2>(aligned, plan, prm, x, out, mask, stream);
+    case 0: return launch_nout<OP, DT, IT, 0>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
+    case 1: return launch_nout<OP, DT, IT, 1>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
+    default: return launch_nout<OP, DT, IT, 2>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
   }
+}
+
+// Largest tile (in units, a multiple of 8 so that tiles start on 128-byte lines) whose
+// generator blocks fit `passes` rounds of the workgroup: a tile of T elements cut by B run
+// boundaries touches at most T/4 + 1.5 (B + 1) blocks, plus one dead slot per boundary when
+// runs differ in phase.  0 = runs too short for tiling.
+uint64_t pick_tile_units(uint64_t run_len, uint64_t V, bool phases_equal) {
+  const uint64_t passes = V / 4;
+  for (uint64_t q = kThreads; q >= 32; q -= 8) {
+    const uint64_t t = q * V;
+    const uint64_t b = (t + run_len - 1) / run_len;
+    const uint64_t blocks = t / 4 + (3 * (b + 1) + 1) / 2 + (phases_equal ? 0 : b) + 1;
+    if (blocks <= passes * kThreads) return q;
+  }
+  return 0;
 }
 
 template <int OP, int DT>
@@ -412,14 +551,21 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   const RunShape rs = run_shape(g);
   constexpr uint64_t V = UnitOf<OP, DT>::kElems;
   const uint64_t pos0 = offset + g.origin;
-  const bool aligned = rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0);
-  // Ragged: one unit per generator block a run can touch; with unequal phases the
-  // count is the upper bound over phases 0..3.
+  Flavour flavour = kRagged;
+  uint64_t tile_units = 0;
+  if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0)) {
+    flavour = kAligned;
+  } else if (rs.run_len >= 16 && kTileable<OP>) {
+    tile_units = pick_tile_units(rs.run_len, V, rs.phases_equal);
+    if (tile_units != 0) flavour = kTiled;
+  }
+  // Aligned: units of V elements.  Otherwise: one unit per generator block a run can touch;
+  // with unequal phases the count is the upper bound over phases 0..3.
   const uint64_t phase_max = rs.phases_equal ? (pos0 % 4) : 3;
-  const uint64_t units = aligned ? rs.run_len / V : (phase_max + rs.run_len + 3) / 4;
+  const uint64_t units = flavour == kAligned ? rs.run_len / V : (phase_max + rs.run_len + 3) / 4;
   if (fits_32bit(rs, units))
-    return launch_typed<OP, DT, uint32_t>(aligned, g, rs, offset, units, prm, x, out, mask, stream);
-  return launch_typed<OP, DT, uint64_t>(aligned, g, rs, offset, units, prm, x, out, mask, stream);
+    return launch_typed<OP, DT, uint32_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
+  return launch_typed<OP, DT, uint64_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
 }
 
 }  // namespace
