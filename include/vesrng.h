@@ -51,7 +51,7 @@ typedef enum {
   VESRNG_ERR_OFFSET_ALIGN = 6,  /* offset is not a multiple of 4 */
   VESRNG_ERR_BAD_PARAM = 7,     /* p outside [0,1], std < 0, high < low, NaN, bad range */
   VESRNG_ERR_DTYPE = 8,         /* dtype not supported by this entry point */
-  VESRNG_ERR_UNSUPPORTED = 9,   /* a valid description this build cannot decode in closed form */
+  VESRNG_ERR_UNSUPPORTED = 9,   /* more than 8 sharding placements on one tensor dimension */
   VESRNG_ERR_OVERFLOW = 10,     /* offset + global numel does not fit 64 bits, or bad stride */
   VESRNG_ERR_HIP = 11,          /* the HIP runtime refused the launch */
   VESRNG_ERR_ALIGN = 12         /* a device pointer is not 16-byte aligned */
@@ -108,6 +108,12 @@ VESRNG_API vesrng_status vesrng_advance_offset(const vesrng_sharding* s, uint64_
  * Both arrays are host memory of n entries; indices must be < local_numel. */
 VESRNG_API vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int64_t* local_index,
                                   uint64_t* global_index);
+
+/* Host only, test hook.  The same map evaluated by the general route (each coordinate is
+ * mapped back through the placements one by one), which the library uses on the device for
+ * shards that are not boxes, e.g. an interleaved dimension cut again across its groups. */
+VESRNG_API vesrng_status vesrng_global_index_general(const vesrng_sharding* s, int64_t n,
+                                                     const int64_t* local_index, uint64_t* global_index);
 
 /* Raw 32-bit draws: out[i] = word (p % 4) of block (p / 4), p = offset + j(i).  Test hook. */
 VESRNG_API vesrng_status vesrng_raw_u32(const vesrng_sharding* s, uint64_t seed, uint64_t offset,

@@ -58,7 +58,7 @@ def lib():
         L.oracle_float_from_bf16.restype = C.c_float
         L.oracle_float_from_bf16.argtypes = [C.c_uint16]
         L.oracle_advance_offset.restype = C.c_uint64
-        L.oracle_advance_offset.argtypes = [C.POINTER(C.c_int64), C.c_int32, C.c_uint64]
+        L.oracle_advance_offset.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_uint64]
         _lib = L
     return _lib
 
@@ -231,6 +231,7 @@ def dropout(sharding, dtype, p, seed, offset, x, i_begin=0, i_end=-1, threads=1,
     return y[:n].reshape(shp), (mask[:n].reshape(shp) if want_mask else None)
 
 
-def advance_offset(global_shape, offset):
+def advance_offset(global_shape, offset, global_stride=None):
     a = (C.c_int64 * max(1, len(global_shape)))(*global_shape)
-    return lib().oracle_advance_offset(a, len(global_shape), offset)
+    st = None if global_stride is None else (C.c_int64 * max(1, len(global_shape)))(*global_stride)
+    return lib().oracle_advance_offset(a, st, len(global_shape), offset)

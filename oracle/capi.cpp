@@ -209,8 +209,11 @@ int oracle_randint(const FlatSharding* f, int64_t low, int64_t high, uint64_t se
   });
 }
 
-uint64_t oracle_advance_offset(const int64_t* global_shape, int32_t ndim, uint64_t offset) {
-  return advance_offset(std::vector<int64_t>(global_shape, global_shape + ndim), offset);
+uint64_t oracle_advance_offset(const int64_t* global_shape, const int64_t* global_stride, int32_t ndim,
+                               uint64_t offset) {
+  std::vector<int64_t> stride;
+  if (global_stride) stride.assign(global_stride, global_stride + ndim);
+  return advance_offset(std::vector<int64_t>(global_shape, global_shape + ndim), stride, offset);
 }
 
 }  // extern "C"

@@ -170,10 +170,18 @@ void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64
   });
 }
 
-uint64_t advance_offset(const std::vector<int64_t>& global_shape, uint64_t offset) {
+uint64_t advance_offset(const std::vector<int64_t>& global_shape, const std::vector<int64_t>& global_stride,
+                        uint64_t offset) {
   uint64_t n = 1;
   for (int64_t e : global_shape) n *= static_cast<uint64_t>(e);
-  return offset + 4 * ((n + 3) / 4);
+  uint64_t span = n;
+  if (n != 0 && !global_stride.empty()) {
+    uint64_t last = 0;  // flat index of the last element
+    for (size_t d = 0; d < global_shape.size(); ++d)
+      last += static_cast<uint64_t>(global_shape[d] - 1) * static_cast<uint64_t>(global_stride[d]);
+    span = last + 1;
+  }
+  return offset + 4 * ((span + 3) / 4);
 }
 
 }  // namespace oracle

@@ -53,7 +53,10 @@ void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64
              int64_t i_begin, int64_t i_end, int64_t* out);
 
 // Offset after an operator on a tensor of the given GLOBAL shape: one draw per
-// global element, rounded up to a whole generator block.
-uint64_t advance_offset(const std::vector<int64_t>& global_shape, uint64_t offset);
+// stream position the whole tensor reaches (= one per element when the tensor is
+// contiguous; up to the largest flat index + 1 under a global stride), rounded up
+// to a whole generator block.
+uint64_t advance_offset(const std::vector<int64_t>& global_shape, const std::vector<int64_t>& global_stride,
+                        uint64_t offset);
 
 }  // namespace oracle

@@ -5,5 +5,5 @@ include/vesrng.h).  PyTorch is used by callers for device memory and streams onl
 """
 from .binding import (  # noqa: F401
     BF16, F32, Sharding, VesrngError, library_path, vesrng_advance_offset, vesrng_dropout,
-    vesrng_global_index, vesrng_local_shape, vesrng_normal, vesrng_randint, vesrng_raw_u32,
+    vesrng_global_index, vesrng_global_index_general, vesrng_local_shape, vesrng_normal, vesrng_randint, vesrng_raw_u32,
     vesrng_status_string, vesrng_uniform)

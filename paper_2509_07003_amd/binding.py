@@ -39,6 +39,7 @@ def _load():
         "vesrng_local_shape": [sp, C.POINTER(i64), C.POINTER(i64)],
         "vesrng_advance_offset": [sp, u64, C.POINTER(u64)],
         "vesrng_global_index": [sp, i64, C.POINTER(i64), C.POINTER(u64)],
+        "vesrng_global_index_general": [sp, i64, C.POINTER(i64), C.POINTER(u64)],
         "vesrng_raw_u32": [sp, u64, u64, vp, vp],
         "vesrng_uniform": [sp, i32, dbl, dbl, u64, u64, vp, vp],
         "vesrng_normal": [sp, i32, dbl, dbl, u64, u64, vp, vp],
@@ -136,6 +137,14 @@ def vesrng_global_index(sharding, local_index):
     src = (C.c_int64 * max(1, n))(*[int(v) for v in local_index])
     dst = (C.c_uint64 * max(1, n))()
     _check(_lib.vesrng_global_index(C.byref(sharding.c), n, src, dst))
+    return list(dst)[:n]
+
+
+def vesrng_global_index_general(sharding, local_index):
+    n = len(local_index)
+    src = (C.c_int64 * max(1, n))(*[int(v) for v in local_index])
+    dst = (C.c_uint64 * max(1, n))()
+    _check(_lib.vesrng_global_index_general(C.byref(sharding.c), n, src, dst))
     return list(dst)[:n]
 
 

@@ -6,7 +6,6 @@ namespace vesrng {
 
 namespace {
 
-constexpr int kMaxDims = 8;
 constexpr uint64_t kMaxNumel = 1ull << 62;
 
 // The global indices a rank holds along ONE tensor dimension, kept as a
@@ -166,30 +165,57 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
     if (pl.kind == VESRNG_INTERLEAVED_SHARD && pl.interleave < 1) return VESRNG_ERR_BAD_PLACEMENT;
   }
 
+  // Two descriptions are built side by side: the chain of placements per dimension (always
+  // possible) and the box form the fast kernels need (dropped as soon as a cut has no box).
   std::vector<DimBox> boxes(static_cast<size_t>(nd));
-  for (int d = 0; d < nd; ++d) boxes[static_cast<size_t>(d)].subs.assign(1, Sub{s->global_shape[d], 1});
+  std::vector<int64_t> length(static_cast<size_t>(nd));
+  for (int d = 0; d < nd; ++d) {
+    boxes[static_cast<size_t>(d)].subs.assign(1, Sub{s->global_shape[d], 1});
+    length[static_cast<size_t>(d)] = s->global_shape[d];
+  }
+  g->boxed = true;
+  g->chain = ChainPlan{};
+  g->chain.ndim = nd;
   for (int m = 0; m < s->mesh_ndim; ++m) {
     const vesrng_placement& pl = s->placements[m];
     if (pl.kind == VESRNG_REPLICATE) continue;
-    DimBox& box = boxes[static_cast<size_t>(pl.dim)];
-    const vesrng_status st =
-        pl.kind == VESRNG_SHARD
-            ? apply_shard(box, s->mesh_shape[m], s->mesh_coord[m])
-            : apply_interleaved(box, pl.interleave, s->mesh_shape[m], s->mesh_coord[m]);
-    if (st != VESRNG_OK) return st;
+    const size_t d = static_cast<size_t>(pl.dim);
+    const int64_t parts = s->mesh_shape[m], which = s->mesh_coord[m];
+    int64_t& n = length[d];
+    ChainStep step{};
+    if (pl.kind == VESRNG_SHARD) {
+      chunk_range(n, parts, which, &step.start, &step.len);
+      n = step.len;
+    } else {
+      if (n % pl.interleave != 0) return VESRNG_ERR_BAD_PLACEMENT;
+      step.interleaved = 1;
+      step.per = n / pl.interleave;
+      chunk_range(step.per, parts, which, &step.start, &step.len);
+      n = step.len * pl.interleave;
+    }
+    if (g->chain.nsteps[d] >= kMaxSteps) return VESRNG_ERR_UNSUPPORTED;
+    g->chain.steps[d][g->chain.nsteps[d]++] = step;
+    if (g->boxed) {
+      const vesrng_status st = pl.kind == VESRNG_SHARD ? apply_shard(boxes[d], parts, which)
+                                                       : apply_interleaved(boxes[d], pl.interleave, parts, which);
+      if (st == VESRNG_ERR_UNSUPPORTED) g->boxed = false;
+      else if (st != VESRNG_OK) return st;
+    }
   }
 
   g->local_shape.assign(static_cast<size_t>(nd), 0);
   g->local_numel = 1;
   for (int d = 0; d < nd; ++d) {
-    g->local_shape[static_cast<size_t>(d)] = boxes[static_cast<size_t>(d)].length();
-    g->local_numel *= g->local_shape[static_cast<size_t>(d)];
+    g->local_shape[static_cast<size_t>(d)] = length[static_cast<size_t>(d)];
+    g->local_numel *= length[static_cast<size_t>(d)];
+    g->chain.local_shape[d] = length[static_cast<size_t>(d)];
+    g->chain.stride[d] = pi[static_cast<size_t>(d)];
   }
   g->global_numel = numel;
   g->max_global_index = max_index;
   g->origin = 0;
   g->axes.clear();
-  if (g->local_numel == 0) return VESRNG_OK;
+  if (g->local_numel == 0 || !g->boxed) return VESRNG_OK;
 
   std::vector<Axis> raw;
   for (int d = 0; d < nd; ++d) {
@@ -206,7 +232,7 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
     else
       g->axes.push_back(a);
   }
-  if (g->axes.size() > static_cast<size_t>(kMaxOuter)) return VESRNG_ERR_UNSUPPORTED;
+  if (g->axes.size() > static_cast<size_t>(kMaxOuter)) g->boxed = false;  // the chain still describes it
   return VESRNG_OK;
 }
 

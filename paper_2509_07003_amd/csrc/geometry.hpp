@@ -24,6 +24,8 @@ struct Geometry {
   uint64_t origin = 0;               // global flat index of local element 0
   std::vector<Axis> axes;            // outermost first; local tensor is row-major over them,
                                      // extent-1 axes dropped, mergeable neighbours merged
+  bool boxed = true;                 // false: the shard is not a box; only `chain` describes it
+  ChainPlan chain{};                 // always filled: the placement-by-placement index map
 };
 
 // Returns VESRNG_OK and fills `g`, or the status that describes what is wrong.

@@ -477,6 +477,35 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
       emit_element<OP, DT>(v[e], prm, xin, li0 + e, out, mask);
 }
 
+// ---- chain kernel: Algorithm 1 element by element ----------------------------------
+// For shards that are not boxes.  One thread per local element: decode, map every
+// coordinate back through the placements, one generator block per element, lane picked.
+template <int OP, int DT>
+__global__ void __launch_bounds__(kThreads)
+chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t local_numel, const OpParams prm,
+             const void* xin, void* out, uint8_t* mask) {
+  const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i >= local_numel) return;
+  const uint64_t p = offset + chain_global_index(cp, i);
+  uint32_t d[4], v[4];
+  philox_block(p >> 2, prm.key0, prm.key1, d);
+  convert_block<OP>(d, prm, v);
+  const uint32_t lane = static_cast<uint32_t>(p) & 3u;
+  const uint32_t value = lane == 0u ? v[0] : lane == 1u ? v[1] : lane == 2u ? v[2] : v[3];
+  emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
+}
+
+template <int OP, int DT>
+hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
+                        uint8_t* mask, hipStream_t stream) {
+  const uint64_t n = static_cast<uint64_t>(g.local_numel);
+  const uint64_t blocks = (n + kThreads - 1) / kThreads;
+  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  hipLaunchKernelGGL((chain_kernel<OP, DT>), dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream,
+                     g.chain, offset, n, prm, x, out, mask);
+  return hipGetLastError();
+}
+
 // ---- dispatch --------------------------------------------------------------------
 enum Flavour { kAligned, kTiled, kRagged };
 // Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
@@ -548,6 +577,7 @@ uint64_t pick_tile_units(uint64_t run_len, uint64_t V, bool phases_equal) {
 template <int OP, int DT>
 hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                      uint8_t* mask, hipStream_t stream) {
+  if (!g.boxed) return launch_chain<OP, DT>(g, offset, prm, x, out, mask, stream);
   const RunShape rs = run_shape(g);
   constexpr uint64_t V = UnitOf<OP, DT>::kElems;
   const uint64_t pos0 = offset + g.origin;

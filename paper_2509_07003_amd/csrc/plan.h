@@ -94,4 +94,53 @@ VESRNG_HD uint64_t run_offset(const PlanT<IT>& p, IT o) {
   return off;
 }
 
+// ---- chain plan: the general index map ---------------------------------------
+// When a rank's indices along some tensor dimension do not form a box (an
+// interleaved dimension that is cut again across group boundaries), the map
+// from a local index to a global index along that dimension is evaluated by
+// undoing the placements one by one, last applied first:
+//   Shard:            c -> start + c
+//   InterleavedShard: c = g * len + t  ->  g * per + start + t
+// (start, len) is the rank's chunk of a list (Shard) or of every group
+// (InterleavedShard); per is the group length before the cut.  This is Algorithm 1
+// element by element: decode i over the local shape, map each coordinate, dot with
+// the global stride.
+constexpr int kMaxDims = 8;
+constexpr int kMaxSteps = 8;
+
+struct ChainStep {
+  int64_t interleaved;  // 0: Shard, 1: InterleavedShard
+  int64_t start, len, per;
+};
+
+struct ChainPlan {
+  int32_t ndim;
+  int32_t nsteps[kMaxDims];
+  int64_t local_shape[kMaxDims];
+  int64_t stride[kMaxDims];  // global stride pi, in elements
+  ChainStep steps[kMaxDims][kMaxSteps];
+};
+
+// Global flat index j of local flat index i.
+VESRNG_HD uint64_t chain_global_index(const ChainPlan& p, uint64_t i) {
+  uint64_t j = 0;
+  for (int d = p.ndim - 1; d >= 0; --d) {
+    const uint64_t n = static_cast<uint64_t>(p.local_shape[d]);
+    const uint64_t q = i / n;
+    int64_t c = static_cast<int64_t>(i - q * n);
+    i = q;
+    for (int m = p.nsteps[d] - 1; m >= 0; --m) {
+      const ChainStep& st = p.steps[d][m];
+      if (st.interleaved) {
+        const int64_t g = c / st.len;
+        c = g * st.per + st.start + (c - g * st.len);
+      } else {
+        c += st.start;
+      }
+    }
+    j += static_cast<uint64_t>(c) * static_cast<uint64_t>(p.stride[d]);
+  }
+  return j;
+}
+
 }  // namespace vesrng

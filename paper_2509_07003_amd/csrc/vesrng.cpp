@@ -103,6 +103,13 @@ vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int
   Geometry g;
   const vesrng_status st = build_geometry(s, &g);
   if (st != VESRNG_OK) return st;
+  if (!g.boxed) {
+    for (int64_t k = 0; k < n; ++k) {
+      if (local_index[k] < 0 || local_index[k] >= g.local_numel) return VESRNG_ERR_BAD_PARAM;
+      global_index[k] = chain_global_index(g.chain, static_cast<uint64_t>(local_index[k]));
+    }
+    return VESRNG_OK;
+  }
   const RunShape rs = run_shape(g);
   // Same plan types and decode routine as the kernels, compiled for the host.
   const bool narrow = fits_32bit(rs, rs.run_len);
@@ -120,6 +127,19 @@ vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int
       const uint64_t run = p64.units_div.div(w);
       global_index[k] = p64.pos0 + run_offset(p64, run) + (w - run * p64.units_per_run);
     }
+  }
+  return VESRNG_OK;
+}
+
+vesrng_status vesrng_global_index_general(const vesrng_sharding* s, int64_t n, const int64_t* local_index,
+                                          uint64_t* global_index) {
+  if (!s || (n > 0 && (!local_index || !global_index))) return VESRNG_ERR_NULL;
+  Geometry g;
+  const vesrng_status st = build_geometry(s, &g);
+  if (st != VESRNG_OK) return st;
+  for (int64_t k = 0; k < n; ++k) {
+    if (local_index[k] < 0 || local_index[k] >= g.local_numel) return VESRNG_ERR_BAD_PARAM;
+    global_index[k] = chain_global_index(g.chain, static_cast<uint64_t>(local_index[k]));
   }
   return VESRNG_OK;
 }
@@ -237,7 +257,7 @@ const char* vesrng_status_string(vesrng_status st) {
     case VESRNG_ERR_OFFSET_ALIGN: return "offset must be a multiple of 4";
     case VESRNG_ERR_BAD_PARAM: return "bad operator parameter";
     case VESRNG_ERR_DTYPE: return "unsupported dtype";
-    case VESRNG_ERR_UNSUPPORTED: return "sharding not decodable in closed form";
+    case VESRNG_ERR_UNSUPPORTED: return "sharding beyond the supported number of placements per dimension";
     case VESRNG_ERR_OVERFLOW: return "stream position or stride overflow";
     case VESRNG_ERR_HIP: return "HIP launch failed";
     case VESRNG_ERR_ALIGN: return "device pointer not 16-byte aligned";

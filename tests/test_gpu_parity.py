@@ -394,3 +394,94 @@ def test_wide_index_path_beyond_2_to_31_local_elements():
     for b, e in ((0, 8192), (ln // 2 - 4096, ln // 2 + 4096), (ln - 8192, ln)):
         want = oracle.raw_u32(args, 22, 1 << 36, i_begin=b, i_end=e).reshape(-1)[b:e]
         assert np.array_equal(out[b:e].cpu().numpy().view(np.uint32), want), (b, e)
+
+
+# ------------------------------------------- general route and global stride ---
+NOT_BOXES = [
+    ([96], [2, 3], [("IS", 0, 2), ("S", 0)]),                       # interleaved, then cut across the groups
+    ([5, 72], [3, 2, 2], [("IS", 1, 4), ("IS", 1, 3), ("S", 1)]),   # interleave on interleave, groups do not nest
+    ([8, 30, 3], [2, 4], [("IS", 1, 5), ("S", 1)]),                 # ragged chunks that straddle groups
+]
+
+
+@pytest.mark.parametrize("op,dtype", [("raw", None), ("uniform", "bf16"), ("normal", "f32"), ("dropout", "bf16"),
+                                       ("dropout", "f32"), ("randint", None)])
+def test_shards_that_are_not_boxes(op, dtype):
+    """Nested / repeated InterleavedShard whose result is not a box takes the element-wise kernel."""
+    seed, offset = 31337, 4096
+    for shape, mesh, pls in NOT_BOXES:
+        shards = {}
+        for c in mesh_coords(mesh):
+            args = (shape, mesh, pls, list(c))
+            what = "%s %s %s" % (op, dtype, args)
+            say(what)
+            if op == "raw":
+                got = gpu_fill("raw", None, args, seed, offset)
+                assert np.array_equal(got, oracle.raw_u32(args, seed, offset)), what
+                shards[c] = got
+            elif op == "randint":
+                assert np.array_equal(gpu_fill("randint", None, args, seed, offset, low=0, high=97),
+                                      oracle.randint(args, 0, 97, seed, offset)), what
+            elif op == "uniform":
+                assert_float_bits_equal(gpu_fill("uniform", dtype, args, seed, offset, low=-1.0, high=1.0),
+                                        oracle.uniform(args, oracle.BF16, -1.0, 1.0, seed, offset), what)
+            elif op == "normal":
+                check_normal(gpu_fill("normal", dtype, args, seed, offset), args, dtype, 0.0, 1.0, seed, offset, what)
+            else:
+                n = oracle.local_shape(*args)[1]
+                xf = W.adversarial_f32(n, seed=n)
+                x = xf if dtype == "f32" else W.bf16_bits_from_f32(xf)
+                y, m = gpu_dropout(dtype, args, 0.25, seed, offset, x)
+                yo, mo = oracle.dropout(args, oracle.F32 if dtype == "f32" else oracle.BF16, 0.25, seed, offset, x)
+                assert np.array_equal(m, mo), what
+                assert_float_bits_equal(y, yo, what)
+        if op == "raw":
+            # Every global element is held by exactly one rank and carries the single-device value.
+            single = gpu_fill("raw", None, (shape, [1], [("R",)], [0]), seed, offset).reshape(-1)
+            seen = np.zeros(single.size, dtype=np.int32)
+            for c, vals in shards.items():
+                j = oracle.global_indices(shape, mesh, pls, list(c)).reshape(-1).astype(np.int64)
+                assert np.array_equal(vals.reshape(-1), single[j])
+                seen[j] += 1
+            assert (seen == 1).all()
+
+
+def test_non_contiguous_global_view():
+    """Algorithm 1 takes the global stride as an input: a transposed (column-major) global tensor
+    and a padded one.  Values follow the global flat index, whatever the local layout."""
+    seed = 77
+    for shape, stride, mesh, pls in [([48, 40], [1, 48], [2, 2], [("S", 0), ("S", 1)]),       # transposed
+                                     ([30, 36], [40, 1], [3], [("S", 1)]),                    # rows padded to 40
+                                     ([6, 10, 12], [1, 6, 60], [2], [("S", 2)])]:             # fully reversed order
+        off = 8
+        for c in mesh_coords(mesh):
+            args = (shape, mesh, pls, list(c), stride)
+            sh = v.Sharding(*args)
+            lshape, n = v.vesrng_local_shape(sh)
+            out = torch.empty(n, dtype=torch.int32, device=DEV)
+            v.vesrng_raw_u32(sh, seed, off, out)
+            got = out.cpu().numpy().view(np.uint32).reshape(lshape)
+            assert np.array_equal(got, oracle.raw_u32(args, seed, off)), args
+            o2 = torch.empty(n, dtype=torch.float32, device=DEV)
+            v.vesrng_normal(sh, v.F32, 0.0, 1.0, seed, off, o2)
+            ref = oracle.normal_f64_values(args, 0.0, 1.0, seed, off).reshape(-1)
+            err = np.abs(o2.cpu().numpy().astype(np.float64) - ref)
+            assert (err <= 1e-6 * np.maximum(np.abs(ref), 1.0)).all(), args
+        nxt = v.vesrng_advance_offset(v.Sharding(shape, mesh, pls, [0] * len(mesh), stride), off)
+        assert nxt == oracle.advance_offset(shape, off, stride)
+
+
+def test_dropout_backward_regenerates_the_mask():
+    """Mask-free dropout: with mask = NULL the pass moves 4 B/element instead of 5, and the
+    backward pass is the same call on the incoming gradient with the forward's (seed, offset):
+    it regenerates the keep decisions instead of reading a stored mask."""
+    args = ([64, 96, 50], [4], [("S", 1)], [2])
+    n = oracle.local_shape(*args)[1]
+    rng = np.random.default_rng(5)
+    x = W.bf16_bits_from_f32(rng.standard_normal(n).astype(np.float32))
+    gy = W.bf16_bits_from_f32(rng.standard_normal(n).astype(np.float32))
+    y, m = gpu_dropout("bf16", args, 0.2, 999, 64, x)
+    gx, _ = gpu_dropout("bf16", args, 0.2, 999, 64, gy, with_mask=False)
+    gxo, mo = oracle.dropout(args, oracle.BF16, 0.2, 999, 64, gy)
+    assert np.array_equal(gx, gxo) and np.array_equal(m, mo)
+    assert not gx[m == 0].any() and (gx[m == 1] != 0).mean() > 0.99

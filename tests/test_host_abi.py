@@ -38,7 +38,10 @@ MESHES = [[1], [2], [3], [4], [2, 2], [2, 3], [3, 2], [4, 2], [2, 2, 2]]
 
 
 def test_geometry_and_decode_plan_match_the_oracle_brute_force():
-    supported = unsupported = 0
+    """Every rank of every mesh / placement assignment: local shape and the i -> j map of the
+    kernels' decode plan (box form where the shard is a box, else the placement chain) and of
+    the general route alone, against the oracle's simulated index lists."""
+    checked = 0
     for shape in SHAPES:
         for mesh in MESHES:
             for pls in all_placements(len(shape), len(mesh)):
@@ -48,24 +51,29 @@ def test_geometry_and_decode_plan_match_the_oracle_brute_force():
                     except oracle.OracleError:
                         with pytest.raises(v.VesrngError) as e:
                             v.vesrng_local_shape(v.Sharding(shape, mesh, pls, c))
-                        # (an earlier mesh dimension may already be out of closed-form reach)
-                        assert e.value.status in (5, 9)
+                        assert e.value.status == 5
                         continue
                     sh = v.Sharding(shape, mesh, pls, c)
-                    try:
-                        got_shape, got_n = v.vesrng_local_shape(sh)
-                    except v.VesrngError as e:
-                        # Only an interleaved dimension that is cut again may be out of reach.
-                        assert e.status == 9 and any(p[0] == "IS" for p in pls), (shape, mesh, pls, c)
-                        unsupported += 1
-                        continue
-                    supported += 1
-                    assert (got_shape, got_n) == (want_shape, want_n), (shape, mesh, pls, c)
+                    assert v.vesrng_local_shape(sh) == (want_shape, want_n), (shape, mesh, pls, c)
+                    checked += 1
                     if want_n:
-                        want_j = oracle.global_indices(shape, mesh, list(pls), list(c)).reshape(-1)
-                        got_j = v.vesrng_global_index(sh, range(want_n))
-                        assert list(want_j) == got_j, (shape, mesh, pls, c)
-    assert supported > 20000 and unsupported < supported // 10
+                        want_j = list(oracle.global_indices(shape, mesh, list(pls), list(c)).reshape(-1))
+                        assert v.vesrng_global_index(sh, range(want_n)) == want_j, (shape, mesh, pls, c)
+                        assert v.vesrng_global_index_general(sh, range(want_n)) == want_j, (shape, mesh, pls, c)
+    assert checked > 29000
+
+
+def test_shards_that_are_not_boxes_take_the_general_route():
+    # 12 entries in 2 groups, cut in 2, then the 6 survivors cut in 3: rank (1,1) holds {5, 9}.
+    sh = v.Sharding([12], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1])
+    assert v.vesrng_local_shape(sh) == ([2], 2)
+    assert v.vesrng_global_index(sh, [0, 1]) == [5, 9]
+    # Interleave on an already interleaved dimension whose groups do not nest.
+    args = ([4, 36], [3, 2, 2], [("IS", 1, 4), ("IS", 1, 3), ("S", 1)], [2, 1, 0])
+    sh = v.Sharding(*args)
+    n = v.vesrng_local_shape(sh)[1]
+    assert n == oracle.local_shape(*args)[1] and n > 0
+    assert v.vesrng_global_index(sh, range(n)) == list(oracle.global_indices(*args).reshape(-1))
 
 
 def test_plain_shard_and_replicate_are_always_supported():
