@@ -90,6 +90,12 @@ typedef struct {
   const int32_t* mesh_shape;          /* [mesh_ndim] */
   const vesrng_placement* placements; /* [mesh_ndim] */
   const int32_t* mesh_coord;          /* [mesh_ndim], coordinate of the rank to generate for */
+  uint64_t virtual_threads;           /* Algorithm 1's global thread count Theta.  0 (default) = one flat
+                                         stream, position offset + j.  Theta > 0 = the algorithm to the
+                                         letter: virtual thread tau = j mod Theta, virtual offset
+                                         beta = offset + j / Theta, generator counter (lo32 q, hi32 q,
+                                         lo32 tau, hi32 tau) with q = beta / 4, output word beta mod 4;
+                                         one generator call per element (slower: not the tuned path). */
 } vesrng_sharding;
 
 /* Host only.  Local shape (Algorithm 1's upsilon) and element count of the
@@ -99,7 +105,9 @@ VESRNG_API vesrng_status vesrng_local_shape(const vesrng_sharding* s, int64_t* l
 
 /* Host only.  The offset every rank must use for the next operator: one draw
  * per GLOBAL element, rounded up to a whole generator block
- * (new = offset + 4 * ceil(global_numel / 4)); mesh, placements and coordinate
+ * (new = offset + 4 * ceil(span / 4), span = largest global flat index + 1, i.e. the
+ * element count of a contiguous tensor; with virtual_threads = Theta > 0, span =
+ * ceil(that / Theta) steps per virtual thread); mesh, placements and coordinate
  * are ignored, so all ranks step together (Section 5, design (f)). */
 VESRNG_API vesrng_status vesrng_advance_offset(const vesrng_sharding* s, uint64_t offset, uint64_t* new_offset);
 

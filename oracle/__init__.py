@@ -11,6 +11,9 @@ A sharding is described with plain Python values:
   placements    one per mesh dimension: ("R",), ("S", dim) or ("IS", dim, groups)
   mesh_coord    list of ints, this rank's coordinate in the mesh
   global_stride optional list of ints (elements); None = row-major contiguous
+  virtual_threads optional int: Algorithm 1's global thread count; 0 = one flat stream
+A "sharding" argument of the bulk functions is the tuple
+(global_shape, mesh_shape, placements, mesh_coord[, global_stride[, virtual_threads]]).
 bfloat16 data travels as numpy uint16 bit patterns.
 """
 import ctypes as C
@@ -30,7 +33,7 @@ class _Flat(C.Structure):
                 ("global_stride", C.POINTER(C.c_int64)), ("mesh_ndim", C.c_int32),
                 ("mesh_shape", C.POINTER(C.c_int32)), ("kind", C.POINTER(C.c_int32)),
                 ("dim", C.POINTER(C.c_int32)), ("interleave", C.POINTER(C.c_int32)),
-                ("mesh_coord", C.POINTER(C.c_int32))]
+                ("mesh_coord", C.POINTER(C.c_int32)), ("virtual_threads", C.c_uint64)]
 
 
 def lib():
@@ -58,7 +61,8 @@ def lib():
         L.oracle_float_from_bf16.restype = C.c_float
         L.oracle_float_from_bf16.argtypes = [C.c_uint16]
         L.oracle_advance_offset.restype = C.c_uint64
-        L.oracle_advance_offset.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_uint64]
+        L.oracle_advance_offset.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_uint64,
+                                            C.c_uint64]
         _lib = L
     return _lib
 
@@ -67,7 +71,7 @@ class OracleError(ValueError):
     pass
 
 
-def _flat(global_shape, mesh_shape, placements, mesh_coord, global_stride=None):
+def _flat(global_shape, mesh_shape, placements, mesh_coord, global_stride=None, virtual_threads=0):
     nd, md = len(global_shape), len(mesh_shape)
     keep = []
 
@@ -87,7 +91,7 @@ def _flat(global_shape, mesh_shape, placements, mesh_coord, global_stride=None):
     f = _Flat(nd, arr(C.c_int64, list(global_shape)),
               arr(C.c_int64, list(global_stride)) if global_stride is not None else None,
               md, arr(C.c_int32, list(mesh_shape)), arr(C.c_int32, kinds), arr(C.c_int32, dims),
-              arr(C.c_int32, inter), arr(C.c_int32, list(mesh_coord)))
+              arr(C.c_int32, inter), arr(C.c_int32, list(mesh_coord)), virtual_threads)
     return f, keep
 
 
@@ -173,8 +177,9 @@ def global_indices(global_shape, mesh_shape, placements, mesh_coord, global_stri
 def _bulk(name, sharding, np_dtype, head_args, i_begin, i_end, threads, out=None):
     global_shape, mesh_shape, placements, mesh_coord = sharding[:4]
     stride = sharding[4] if len(sharding) > 4 else None
+    theta = sharding[5] if len(sharding) > 5 else 0
     shp, n = local_shape(global_shape, mesh_shape, placements, mesh_coord)
-    f, _k = _flat(global_shape, mesh_shape, placements, mesh_coord, stride)
+    f, _k = _flat(global_shape, mesh_shape, placements, mesh_coord, stride, theta)
     if out is None:
         out = np.zeros(max(1, n), dtype=np_dtype)
     _call(getattr(lib(), name), C.byref(f), *head_args, _ptr(out), C.c_int64(i_begin),
@@ -216,12 +221,13 @@ def dropout(sharding, dtype, p, seed, offset, x, i_begin=0, i_end=-1, threads=1,
     Returns (y, mask); elements outside [i_begin, i_end) are left zero."""
     global_shape, mesh_shape, placements, mesh_coord = sharding[:4]
     stride = sharding[4] if len(sharding) > 4 else None
+    theta = sharding[5] if len(sharding) > 5 else 0
     shp, n = local_shape(global_shape, mesh_shape, placements, mesh_coord)
     npdt = np.float32 if dtype == F32 else np.uint16
     x = np.ascontiguousarray(x, dtype=npdt).reshape(-1)
     if x.size != n:
         raise OracleError("x must hold exactly the local shard")
-    f, _k = _flat(global_shape, mesh_shape, placements, mesh_coord, stride)
+    f, _k = _flat(global_shape, mesh_shape, placements, mesh_coord, stride, theta)
     y = np.zeros(max(1, n), dtype=npdt)
     mask = np.zeros(max(1, n), dtype=np.uint8) if want_mask else None
     xs = x if x.size else np.zeros(1, dtype=npdt)
@@ -231,7 +237,7 @@ def dropout(sharding, dtype, p, seed, offset, x, i_begin=0, i_end=-1, threads=1,
     return y[:n].reshape(shp), (mask[:n].reshape(shp) if want_mask else None)
 
 
-def advance_offset(global_shape, offset, global_stride=None):
+def advance_offset(global_shape, offset, global_stride=None, virtual_threads=0):
     a = (C.c_int64 * max(1, len(global_shape)))(*global_shape)
     st = None if global_stride is None else (C.c_int64 * max(1, len(global_shape)))(*global_stride)
-    return lib().oracle_advance_offset(a, st, len(global_shape), offset)
+    return lib().oracle_advance_offset(a, st, len(global_shape), offset, virtual_threads)

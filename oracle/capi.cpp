@@ -29,6 +29,7 @@ struct FlatSharding {
   const int32_t* placement_dim;         // [mesh_ndim]
   const int32_t* placement_interleave;  // [mesh_ndim]
   const int32_t* mesh_coord;
+  uint64_t virtual_threads;
 };
 
 Sharding unflatten(const FlatSharding* f) {
@@ -37,6 +38,7 @@ Sharding unflatten(const FlatSharding* f) {
   if (f->global_stride) s.global_stride.assign(f->global_stride, f->global_stride + f->ndim);
   s.mesh_shape.assign(f->mesh_shape, f->mesh_shape + f->mesh_ndim);
   s.mesh_coord.assign(f->mesh_coord, f->mesh_coord + f->mesh_ndim);
+  s.virtual_threads = f->virtual_threads;
   for (int m = 0; m < f->mesh_ndim; ++m)
     s.placements.push_back(Placement{f->placement_kind[m], f->placement_dim[m], f->placement_interleave[m]});
   return s;
@@ -210,10 +212,10 @@ int oracle_randint(const FlatSharding* f, int64_t low, int64_t high, uint64_t se
 }
 
 uint64_t oracle_advance_offset(const int64_t* global_shape, const int64_t* global_stride, int32_t ndim,
-                               uint64_t offset) {
+                               uint64_t offset, uint64_t virtual_threads) {
   std::vector<int64_t> stride;
   if (global_stride) stride.assign(global_stride, global_stride + ndim);
-  return advance_offset(std::vector<int64_t>(global_shape, global_shape + ndim), stride, offset);
+  return advance_offset(std::vector<int64_t>(global_shape, global_shape + ndim), stride, offset, virtual_threads);
 }
 
 }  // extern "C"

@@ -22,6 +22,12 @@ float float_of(uint32_t b) {
   return f;
 }
 
+// The draw of global element j.
+uint32_t draw_at(const Sharding& s, uint64_t seed, uint64_t offset, uint64_t j) {
+  const Slot slot = slot_of(offset, j, s.virtual_threads);
+  return draw_word(seed, slot, slot.word);
+}
+
 // 24 random bits as a fraction k / 2^24, exactly representable in fp32.
 float fraction24(uint32_t x) { return static_cast<float>(x >> 8) * 0x1p-24f; }
 
@@ -103,33 +109,35 @@ float dropout_scale(double p) { return static_cast<float>(1.0 / (1.0 - p)); }
 void raw_u32(const Sharding& s, uint64_t seed, uint64_t offset, int64_t i_begin, int64_t i_end,
              uint32_t* out) {
   for_each_local(s, i_begin, i_end,
-                 [&](int64_t i, uint64_t j) { out[i] = draw(seed, position(offset, j)); });
+                 [&](int64_t i, uint64_t j) { out[i] = draw_at(s, seed, offset, j); });
 }
 
 void uniform(const Sharding& s, DType dt, double low, double high, uint64_t seed, uint64_t offset,
              int64_t i_begin, int64_t i_end, void* out) {
   const float lo = static_cast<float>(low), hi = static_cast<float>(high);
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
-    const uint32_t x = draw(seed, position(offset, j));
+    const uint32_t x = draw_at(s, seed, offset, j);
     if (dt == kF32) static_cast<float*>(out)[i] = uniform_f32(x, lo, hi);
     else static_cast<uint16_t*>(out)[i] = uniform_bf16(x, lo, hi);
   });
 }
 
-// The element at stream position p uses the draw pair of its half-block: words
-// (0,1) for p % 4 in {0,1}, words (2,3) for p % 4 in {2,3}; the first word of
-// the pair feeds the radius, the second the angle; even p takes the cosine.
-static double normal_at(uint64_t seed, uint64_t p, double mean, double std) {
-  const uint64_t pair_base = p - (p % 2);
-  const uint32_t xa = draw(seed, pair_base);
-  const uint32_t xb = draw(seed, pair_base + 1);
-  return normal_f64(xa, xb, (p % 2) == 1, mean, std);
+// An element whose draw is word w of a block uses the draw pair of its half-block:
+// words (0,1) for w in {0,1}, words (2,3) for w in {2,3}; the first word of the pair
+// feeds the radius, the second the angle; an even word takes the cosine.  (In the
+// flat stream w = p % 4, so neighbouring positions 2k, 2k+1 share a pair.)
+static double normal_at(const Sharding& s, uint64_t seed, uint64_t offset, uint64_t j, double mean, double std) {
+  const Slot slot = slot_of(offset, j, s.virtual_threads);
+  const uint32_t even_word = slot.word - (slot.word % 2);
+  const uint32_t xa = draw_word(seed, slot, even_word);
+  const uint32_t xb = draw_word(seed, slot, even_word + 1);
+  return normal_f64(xa, xb, (slot.word % 2) == 1, mean, std);
 }
 
 void normal(const Sharding& s, DType dt, double mean, double std, uint64_t seed, uint64_t offset,
             int64_t i_begin, int64_t i_end, void* out) {
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
-    const double v = normal_at(seed, position(offset, j), mean, std);
+    const double v = normal_at(s, seed, offset, j, mean, std);
     if (dt == kF32) static_cast<float*>(out)[i] = static_cast<float>(v);
     else static_cast<uint16_t*>(out)[i] = bf16_from_double(v);
   });
@@ -138,7 +146,7 @@ void normal(const Sharding& s, DType dt, double mean, double std, uint64_t seed,
 void normal_f64_values(const Sharding& s, double mean, double std, uint64_t seed, uint64_t offset,
                        int64_t i_begin, int64_t i_end, double* out) {
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
-    out[i] = normal_at(seed, position(offset, j), mean, std);
+    out[i] = normal_at(s, seed, offset, j, mean, std);
   });
 }
 
@@ -147,7 +155,7 @@ void dropout(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offs
   const uint32_t threshold = dropout_threshold(p);
   const float scale = dropout_scale(p);
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
-    const uint32_t r = draw(seed, position(offset, j));
+    const uint32_t r = draw_at(s, seed, offset, j);
     const bool keep = (r >> 8) < threshold;
     if (mask) mask[i] = keep ? 1 : 0;
     if (dt == kF32) {
@@ -165,13 +173,13 @@ void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64
              int64_t i_begin, int64_t i_end, int64_t* out) {
   const uint64_t range = static_cast<uint64_t>(high - low);
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
-    const uint64_t r = draw(seed, position(offset, j));
+    const uint64_t r = draw_at(s, seed, offset, j);
     out[i] = low + static_cast<int64_t>(r % range);
   });
 }
 
 uint64_t advance_offset(const std::vector<int64_t>& global_shape, const std::vector<int64_t>& global_stride,
-                        uint64_t offset) {
+                        uint64_t offset, uint64_t virtual_threads) {
   uint64_t n = 1;
   for (int64_t e : global_shape) n *= static_cast<uint64_t>(e);
   uint64_t span = n;
@@ -181,6 +189,8 @@ uint64_t advance_offset(const std::vector<int64_t>& global_shape, const std::vec
       last += static_cast<uint64_t>(global_shape[d] - 1) * static_cast<uint64_t>(global_stride[d]);
     span = last + 1;
   }
+  // With theta virtual threads every thread steps ceil(span / theta) times.
+  if (virtual_threads != 0) span = (span + virtual_threads - 1) / virtual_threads;
   return offset + 4 * ((span + 3) / 4);
 }
 

@@ -14,8 +14,6 @@ namespace oracle {
 enum DType : int32_t { kF32 = 0, kBF16 = 1 };
 
 // --- value of ONE global element -------------------------------------------
-// Stream position of global element j under a call's offset.
-inline uint64_t position(uint64_t offset, uint64_t j) { return offset + j; }
 
 // Uniform in [low, high): top 24 bits of the draw scaled by 2^-24 (exact in
 // fp32), then u * (high - low) + low as two separately rounded fp32 operations;
@@ -57,6 +55,6 @@ void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64
 // contiguous; up to the largest flat index + 1 under a global stride), rounded up
 // to a whole generator block.
 uint64_t advance_offset(const std::vector<int64_t>& global_shape, const std::vector<int64_t>& global_stride,
-                        uint64_t offset);
+                        uint64_t offset, uint64_t virtual_threads = 0);
 
 }  // namespace oracle

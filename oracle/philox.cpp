@@ -44,4 +44,32 @@ uint32_t draw(uint64_t seed, uint64_t p) {
   return philox4x32_10(ctr, key).w[p % 4];
 }
 
+Slot slot_of(uint64_t offset, uint64_t j, uint64_t theta) {
+  Slot s;
+  if (theta == 0) {
+    const uint64_t p = offset + j;
+    const uint64_t b = p / 4;
+    s.ctr[0] = static_cast<uint32_t>(b);
+    s.ctr[1] = static_cast<uint32_t>(b >> 32);
+    s.ctr[2] = 0;
+    s.ctr[3] = 0;
+    s.word = static_cast<uint32_t>(p % 4);
+  } else {
+    const uint64_t tau = j % theta;
+    const uint64_t beta = offset + j / theta;
+    const uint64_t q = beta / 4;
+    s.ctr[0] = static_cast<uint32_t>(q);
+    s.ctr[1] = static_cast<uint32_t>(q >> 32);
+    s.ctr[2] = static_cast<uint32_t>(tau);
+    s.ctr[3] = static_cast<uint32_t>(tau >> 32);
+    s.word = static_cast<uint32_t>(beta % 4);
+  }
+  return s;
+}
+
+uint32_t draw_word(uint64_t seed, const Slot& slot, uint32_t word) {
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  return philox4x32_10(slot.ctr, key).w[word];
+}
+
 }  // namespace oracle

@@ -27,6 +27,7 @@ struct Sharding {
   std::vector<int32_t> mesh_shape;
   std::vector<Placement> placements;   // one per mesh dimension, dim 0 applied first
   std::vector<int32_t> mesh_coord;
+  uint64_t virtual_threads = 0;        // Algorithm 1's global thread count; 0 = one flat stream
 };
 
 // For every tensor dimension, the global indices this rank holds, in local order.

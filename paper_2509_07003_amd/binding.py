@@ -22,7 +22,7 @@ class _Sharding(C.Structure):
     _fields_ = [("ndim", C.c_int32), ("global_shape", C.POINTER(C.c_int64)),
                 ("global_stride", C.POINTER(C.c_int64)), ("mesh_ndim", C.c_int32),
                 ("mesh_shape", C.POINTER(C.c_int32)), ("placements", C.POINTER(_Placement)),
-                ("mesh_coord", C.POINTER(C.c_int32))]
+                ("mesh_coord", C.POINTER(C.c_int32)), ("virtual_threads", C.c_uint64)]
 
 
 def library_path():
@@ -71,9 +71,10 @@ def vesrng_status_string(status):
 class Sharding:
     """Host-side description: global shape, mesh shape, one placement per mesh dimension
     (("R",), ("S", dim), ("IS", dim, groups) or ("P",)), the rank's mesh coordinate and
-    optionally the global stride in elements."""
+    optionally the global stride in elements and Algorithm 1's global thread count (0 = flat stream)."""
 
-    def __init__(self, global_shape, mesh_shape=(), placements=(), mesh_coord=(), global_stride=None):
+    def __init__(self, global_shape, mesh_shape=(), placements=(), mesh_coord=(), global_stride=None,
+                 virtual_threads=0):
         self.global_shape = [int(v) for v in global_shape]
         self.mesh_shape = [int(v) for v in mesh_shape]
         self.placements = [tuple(p) for p in placements]
@@ -89,10 +90,12 @@ class Sharding:
         self._pl = (_Placement * max(1, md))()
         for m, p in enumerate(self.placements):
             self._pl[m] = _Placement(_KIND[p[0]], p[1] if len(p) > 1 else 0, p[2] if len(p) > 2 else 1)
-        self.c = _Sharding(nd, self._shape, self._stride, md, self._mesh, self._pl, self._coord)
+        self.virtual_threads = int(virtual_threads)
+        self.c = _Sharding(nd, self._shape, self._stride, md, self._mesh, self._pl, self._coord, self.virtual_threads)
 
     def with_coord(self, mesh_coord):
-        return Sharding(self.global_shape, self.mesh_shape, self.placements, mesh_coord, self.global_stride)
+        return Sharding(self.global_shape, self.mesh_shape, self.placements, mesh_coord, self.global_stride,
+                        self.virtual_threads)
 
 
 def _check(status):

@@ -24,6 +24,7 @@ struct Geometry {
   uint64_t origin = 0;               // global flat index of local element 0
   std::vector<Axis> axes;            // outermost first; local tensor is row-major over them,
                                      // extent-1 axes dropped, mergeable neighbours merged
+  uint64_t virtual_threads = 0;      // Algorithm 1's global thread count Theta; 0 = flat stream
   bool boxed = true;                 // false: the shard is not a box; only `chain` describes it
   ChainPlan chain{};                 // always filled: the placement-by-placement index map
 };

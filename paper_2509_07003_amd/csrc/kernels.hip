@@ -64,9 +64,9 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
   return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
-// Philox4x32-10 on counter (lo32 b, hi32 b, 0, 0), key (k0, k1).
-__device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k1, uint32_t (&w)[4]) {
-  uint32_t c0 = static_cast<uint32_t>(b), c1 = static_cast<uint32_t>(b >> 32), c2 = 0u, c3 = 0u;
+// Philox4x32-10 on counter (c0, c1, c2, c3), key (k0, k1).
+__device__ __forceinline__ void philox_rounds(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&w)[4]) {
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
     const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
@@ -84,6 +84,11 @@ __device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k
   w[1] = c1;
   w[2] = c2;
   w[3] = c3;
+}
+
+// Block b of the flat stream: counter (lo32 b, hi32 b, 0, 0).
+__device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k1, uint32_t (&w)[4]) {
+  philox_rounds(static_cast<uint32_t>(b), static_cast<uint32_t>(b >> 32), 0u, 0u, k0, k1, w);
 }
 
 // ---- conversions ---------------------------------------------------------------
@@ -478,20 +483,36 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
 }
 
 // ---- chain kernel: Algorithm 1 element by element ----------------------------------
-// For shards that are not boxes.  One thread per local element: decode, map every
-// coordinate back through the placements, one generator block per element, lane picked.
+// For shards that are not boxes, and for the virtual-thread layout.  One thread per local
+// element: decode, map every coordinate back through the placements, one generator block
+// per element, word picked.  theta == 0: flat stream (position offset + j).  theta > 0:
+// Algorithm 1's "virtualize thread index and offset" to the letter - virtual thread
+// tau = j mod theta, virtual offset beta = offset + j / theta, counter
+// (lo32 q, hi32 q, lo32 tau, hi32 tau) with q = beta / 4, word beta mod 4.
 template <int OP, int DT>
 __global__ void __launch_bounds__(kThreads)
-chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t local_numel, const OpParams prm,
-             const void* xin, void* out, uint8_t* mask) {
+chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, const uint64_t local_numel,
+             const OpParams prm, const void* xin, void* out, uint8_t* mask) {
   const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (i >= local_numel) return;
-  const uint64_t p = offset + chain_global_index(cp, i);
+  const uint64_t j = chain_global_index(cp, i);
   uint32_t d[4], v[4];
-  philox_block(p >> 2, prm.key0, prm.key1, d);
+  uint32_t word;
+  if (theta == 0) {
+    const uint64_t p = offset + j;
+    philox_block(p >> 2, prm.key0, prm.key1, d);
+    word = static_cast<uint32_t>(p) & 3u;
+  } else {
+    const uint64_t step = j / theta;
+    const uint64_t tau = j - step * theta;
+    const uint64_t beta = offset + step;
+    const uint64_t q = beta >> 2;
+    philox_rounds(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), static_cast<uint32_t>(tau),
+                  static_cast<uint32_t>(tau >> 32), prm.key0, prm.key1, d);
+    word = static_cast<uint32_t>(beta) & 3u;
+  }
   convert_block<OP>(d, prm, v);
-  const uint32_t lane = static_cast<uint32_t>(p) & 3u;
-  const uint32_t value = lane == 0u ? v[0] : lane == 1u ? v[1] : lane == 2u ? v[2] : v[3];
+  const uint32_t value = word == 0u ? v[0] : word == 1u ? v[1] : word == 2u ? v[2] : v[3];
   emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
 }
 
@@ -502,7 +523,7 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
   const uint64_t blocks = (n + kThreads - 1) / kThreads;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   hipLaunchKernelGGL((chain_kernel<OP, DT>), dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream,
-                     g.chain, offset, n, prm, x, out, mask);
+                     g.chain, offset, g.virtual_threads, n, prm, x, out, mask);
   return hipGetLastError();
 }
 
@@ -577,7 +598,7 @@ uint64_t pick_tile_units(uint64_t run_len, uint64_t V, bool phases_equal) {
 template <int OP, int DT>
 hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                      uint8_t* mask, hipStream_t stream) {
-  if (!g.boxed) return launch_chain<OP, DT>(g, offset, prm, x, out, mask, stream);
+  if (!g.boxed || g.virtual_threads != 0) return launch_chain<OP, DT>(g, offset, prm, x, out, mask, stream);
   const RunShape rs = run_shape(g);
   constexpr uint64_t V = UnitOf<OP, DT>::kElems;
   const uint64_t pos0 = offset + g.origin;

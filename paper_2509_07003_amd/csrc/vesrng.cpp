@@ -52,7 +52,8 @@ vesrng_status prepare(const vesrng_sharding* s, uint64_t seed, uint64_t offset, 
   const vesrng_status st = build_geometry(s, g);
   if (st != VESRNG_OK) return st;
   if (offset % 4 != 0) return VESRNG_ERR_OFFSET_ALIGN;
-  // The last stream position the whole tensor uses must not wrap.
+  // The last stream position the whole tensor uses must not wrap (with virtual threads the
+  // positions are smaller still: offset + j / theta).
   if (g->global_numel != 0 && offset > std::numeric_limits<uint64_t>::max() - g->max_global_index - 4)
     return VESRNG_ERR_OVERFLOW;
   prm->key0 = static_cast<uint32_t>(seed);
@@ -89,8 +90,10 @@ vesrng_status vesrng_advance_offset(const vesrng_sharding* s, uint64_t offset, u
   Geometry g;
   const vesrng_status st = build_geometry(&whole, &g);
   if (st != VESRNG_OK) return st;
-  // Draws consumed: one per position up to the last global element.
-  const uint64_t span = g.global_numel == 0 ? 0 : g.max_global_index + 1;
+  // Draws consumed: one per position up to the last global element; with theta virtual
+  // threads each thread steps ceil(span / theta) times.
+  uint64_t span = g.global_numel == 0 ? 0 : g.max_global_index + 1;
+  if (s->virtual_threads != 0) span = (span + s->virtual_threads - 1) / s->virtual_threads;
   const uint64_t step = 4 * ((span + 3) / 4);
   if (offset > std::numeric_limits<uint64_t>::max() - step) return VESRNG_ERR_OVERFLOW;
   *new_offset = offset + step;

@@ -485,3 +485,46 @@ def test_dropout_backward_regenerates_the_mask():
     gxo, mo = oracle.dropout(args, oracle.BF16, 0.2, 999, 64, gy)
     assert np.array_equal(gx, gxo) and np.array_equal(m, mo)
     assert not gx[m == 0].any() and (gx[m == 1] != 0).mean() > 0.99
+
+
+@pytest.mark.parametrize("theta", [1, 7, 1024, 1 << 40])
+def test_virtual_thread_layout(theta):
+    """Algorithm 1 to the letter (global thread count theta): every operator, sharded, against the oracle."""
+    seed, offset = (0xBEEF << 32) | 17, 1 << 33
+    for shape, mesh, pls in (([129, 67], [2, 3], [("S", 0), ("S", 1)]), ([4, 36, 5], [4], [("IS", 1, 3)])):
+        single = None
+        shards = {}
+        for c in mesh_coords(mesh):
+            args = (shape, mesh, pls, list(c), None, theta)
+            sh = v.Sharding(*args)
+            lshape, n = v.vesrng_local_shape(sh)
+            what = "theta=%d %s" % (theta, args[:4])
+            say(what)
+            out = torch.empty(max(n, 1), dtype=torch.int32, device=DEV)
+            v.vesrng_raw_u32(sh, seed, offset, out)
+            raw = out.cpu().numpy().view(np.uint32)[:n].reshape(lshape)
+            assert np.array_equal(raw, oracle.raw_u32(args, seed, offset)), what
+            shards[c] = raw
+            o2 = torch.empty(max(n, 1), dtype=torch.float32, device=DEV)
+            v.vesrng_normal(sh, v.F32, 0.0, 1.0, seed, offset, o2)
+            ref = oracle.normal_f64_values(args, 0.0, 1.0, seed, offset).reshape(-1)
+            err = np.abs(o2.cpu().numpy()[:n].astype(np.float64) - ref)
+            assert (err <= 1e-6 * np.maximum(np.abs(ref), 1.0)).all(), what
+            o3 = torch.empty(max(n, 1), dtype=torch.bfloat16, device=DEV)
+            v.vesrng_uniform(sh, v.BF16, 0.0, 1.0, seed, offset, o3)
+            assert np.array_equal(o3.view(torch.int16).cpu().numpy().view(np.uint16)[:n].reshape(lshape),
+                                  oracle.uniform(args, oracle.BF16, 0.0, 1.0, seed, offset)), what
+            x = W.bf16_bits_from_f32(W.adversarial_f32(n, seed=n))
+            xd = torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
+            y = torch.empty_like(xd)
+            m = torch.empty(max(n, 1), dtype=torch.uint8, device=DEV)
+            v.vesrng_dropout(sh, v.BF16, 0.5, seed, offset, xd, y, m)
+            yo, mo = oracle.dropout(args, oracle.BF16, 0.5, seed, offset, x)
+            assert np.array_equal(m.cpu().numpy()[:n].reshape(lshape), mo), what
+            assert_float_bits_equal(y.view(torch.int16).cpu().numpy().view(np.uint16)[:n].reshape(lshape), yo, what)
+        sh1 = v.Sharding(shape, [1], [("R",)], [0], None, theta)
+        out = torch.empty(int(np.prod(shape)), dtype=torch.int32, device=DEV)
+        v.vesrng_raw_u32(sh1, seed, offset, out)
+        single = out.cpu().numpy().view(np.uint32).reshape(shape)
+        assert np.array_equal(merge_shards(shards, mesh, pls), single)
+        assert v.vesrng_advance_offset(sh1, offset) == oracle.advance_offset(shape, offset, None, theta)

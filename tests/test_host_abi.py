@@ -136,6 +136,10 @@ def test_advance_offset():
     a = v.vesrng_advance_offset(v.Sharding([10, 10], [4], [("S", 1)], [0]), 16)
     b = v.vesrng_advance_offset(v.Sharding([10, 10], [2, 2], [("R",), ("S", 0)], [1, 1]), 16)
     assert a == b == 116
+    # Virtual-thread layout: ceil(N / theta) steps per thread.
+    for theta in (1, 5, 60, 1 << 40):
+        assert v.vesrng_advance_offset(v.Sharding([6, 10], virtual_threads=theta), 16) == \
+            oracle.advance_offset([6, 10], 16, None, theta)
     with pytest.raises(v.VesrngError) as e:
         v.vesrng_advance_offset(v.Sharding([10]), 3)
     assert e.value.status == 6

@@ -412,3 +412,50 @@ def test_statistics_of_the_three_distributions():
     assert r.min() == -3 and r.max() == 6
     assert stats.chisquare(np.bincount(r + 3, minlength=10)).pvalue > 1e-4
     assert list(oracle.randint(([8], [1], [("R",)], [0]), 10, 17, 5, 0)) == [10 + oracle.draw(5, i) % 7 for i in range(8)]
+
+
+# ------------------------------------------------ virtual-thread layout -------
+def test_virtual_thread_layout_follows_algorithm_1_to_the_letter():
+    """theta > 0: virtual thread tau = j mod theta, virtual offset beta = offset + j / theta,
+    generator called with (seed, tau, beta).  Checked against the big-integer generator."""
+    seed = (0x1234 << 32) | 0xABCDEF01
+    key = [seed % 2 ** 32, seed >> 32]
+    for theta, offset, n in ((1, 0, 40), (7, 8, 100), (64, 4, 300), (1 << 40, 12, 50)):
+        got = oracle.raw_u32(([n], [1], [("R",)], [0], None, theta), seed, offset)
+        for j in (0, 1, 2, n // 2, n - 1):
+            tau, beta = j % theta, offset + j // theta
+            q = beta // 4
+            want = _philox_bigint([q % 2 ** 32, q >> 32, tau % 2 ** 32, tau >> 32], key)[beta % 4]
+            assert int(got[j]) == want, (theta, j)
+    # theta >= numel: every element is its own virtual thread at the call's offset.
+    got = oracle.raw_u32(([10], [1], [("R",)], [0], None, 1000), 5, 8)
+    assert list(got) == [_philox_bigint([2, 0, j, 0], [5, 0])[0] for j in range(10)]
+    # theta = 1: one thread walks the whole tensor - the flat stream again.
+    a = oracle.raw_u32(([37], [1], [("R",)], [0], None, 1), 5, 8)
+    b = oracle.raw_u32(([37], [1], [("R",)], [0]), 5, 8)
+    assert np.array_equal(a, b)
+
+
+def test_virtual_thread_layout_keeps_the_merge_invariant_and_the_offset_rule():
+    seed, offset, theta = 99, 16, 5
+    for shape, mesh, pls in (([6, 10], [2, 2], [("S", 0), ("S", 1)]), ([24], [3], [("IS", 0, 4)]), ([4, 9], [3], [("S", 1)])):
+        single = oracle.raw_u32((shape, [1], [("R",)], [0], None, theta), seed, offset)
+        shards = {c: oracle.raw_u32((shape, mesh, pls, list(c), None, theta), seed, offset) for c in mesh_coords(mesh)}
+        assert np.array_equal(merge_shards(shards, mesh, pls), single)
+        z = oracle.normal_f64_values((shape, [1], [("R",)], [0], None, theta), 0.0, 1.0, seed, offset).reshape(-1)
+        # Elements j and j + theta sit in neighbouring words of one thread's stream: they form a
+        # Box-Muller pair when the lower one's word is even.
+        for j in range(z.size - theta):
+            beta = offset + j // theta
+            if beta % 2 == 0:
+                xa = int(single.reshape(-1)[j]); xb = int(single.reshape(-1)[j + theta])
+                assert z[j] == oracle.normal_f64(xa, xb, False) and z[j + theta] == oracle.normal_f64(xa, xb, True)
+    # Each of theta threads steps ceil(N / theta) times; the offset moves by that, rounded up to 4.
+    assert oracle.advance_offset([6, 10], 16, None, 5) == 16 + 12
+    assert oracle.advance_offset([6, 10], 16, None, 60) == 16 + 4
+    assert oracle.advance_offset([6, 10], 16, None, 1) == 16 + 60
+    # The next call's values do not overlap this call's.
+    nxt = oracle.advance_offset([6, 10], offset, None, theta)
+    a = oracle.raw_u32(([6, 10], [1], [("R",)], [0], None, theta), seed, offset).reshape(-1)
+    b = oracle.raw_u32(([6, 10], [1], [("R",)], [0], None, theta), seed, nxt).reshape(-1)
+    assert not set(a.tolist()) & set(b.tolist())
