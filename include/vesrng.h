@@ -146,10 +146,21 @@ VESRNG_API vesrng_status vesrng_normal(const vesrng_sharding* s, vesrng_dtype dt
 /* Fused dropout (Table 5's nn.Dropout): keep = (draw >> 8) < round((1 - p) * 2^24);
  * y = keep ? round_to_dtype(fl32(x * fl32(1 / (1 - p)))) : +0;  mask = keep (0 / 1).
  * One pass: reads x once, writes y and (if non-NULL) the uint8 mask once.
- * y may alias x exactly (in place).  NaN payloads of kept NaN inputs are unspecified. */
+ * y may alias x exactly (in place).  NaN payloads of kept NaN inputs are unspecified.
+ * Mask-free use: pass mask = NULL (4 instead of 5 bytes per bf16 element).  Backward pass:
+ * the same call on the incoming gradient with the forward's (seed, offset) regenerates the
+ * keep decisions: grad_x = keep ? grad_y * scale : 0; no stored mask is read. */
 VESRNG_API vesrng_status vesrng_dropout(const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
                              uint64_t offset, const void* x, void* y, uint8_t* mask,
                              void* hip_stream);
+
+/* Fused dropout + residual add (the step that follows dropout in a transformer block):
+ * y = round_to_dtype(fl32(residual + (keep ? fl32(x * scale) : +0))), keep / scale / mask as in
+ * vesrng_dropout.  One pass: reads x and residual once, writes y and (if non-NULL) mask once.
+ * residual is a device pointer with the shape and dtype of x; y may alias x or residual. */
+VESRNG_API vesrng_status vesrng_dropout_add(const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
+                                 uint64_t offset, const void* x, const void* residual, void* y,
+                                 uint8_t* mask, void* hip_stream);
 
 /* Integers in [low, high), 0 < high - low <= 2^32: out = low + draw mod (high - low),
  * stored as int64 (Table 5's randint_like). */

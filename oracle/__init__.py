@@ -237,6 +237,27 @@ def dropout(sharding, dtype, p, seed, offset, x, i_begin=0, i_end=-1, threads=1,
     return y[:n].reshape(shp), (mask[:n].reshape(shp) if want_mask else None)
 
 
+def dropout_add(sharding, dtype, p, seed, offset, x, residual, threads=1):
+    """y = residual + dropout(x) with one rounding to the dtype at the end.  Returns (y, mask)."""
+    global_shape, mesh_shape, placements, mesh_coord = sharding[:4]
+    stride = sharding[4] if len(sharding) > 4 else None
+    theta = sharding[5] if len(sharding) > 5 else 0
+    shp, n = local_shape(global_shape, mesh_shape, placements, mesh_coord)
+    npdt = np.float32 if dtype == F32 else np.uint16
+    x = np.ascontiguousarray(x, dtype=npdt).reshape(-1)
+    residual = np.ascontiguousarray(residual, dtype=npdt).reshape(-1)
+    if x.size != n or residual.size != n:
+        raise OracleError("x and residual must hold exactly the local shard")
+    f, _k = _flat(global_shape, mesh_shape, placements, mesh_coord, stride, theta)
+    y = np.zeros(max(1, n), dtype=npdt)
+    mask = np.zeros(max(1, n), dtype=np.uint8)
+    pad = np.zeros(1, dtype=npdt)
+    _call(lib().oracle_dropout_add, C.byref(f), C.c_int32(dtype), C.c_double(p), C.c_uint64(seed),
+          C.c_uint64(offset), _ptr(x if n else pad), _ptr(residual if n else pad), _ptr(y), _ptr(mask),
+          C.c_int64(0), C.c_int64(-1), C.c_int(threads))
+    return y[:n].reshape(shp), mask[:n].reshape(shp)
+
+
 def advance_offset(global_shape, offset, global_stride=None, virtual_threads=0):
     a = (C.c_int64 * max(1, len(global_shape)))(*global_shape)
     st = None if global_stride is None else (C.c_int64 * max(1, len(global_shape)))(*global_stride)

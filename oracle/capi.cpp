@@ -199,6 +199,17 @@ int oracle_dropout(const FlatSharding* f, int32_t dtype, double p, uint64_t seed
   });
 }
 
+int oracle_dropout_add(const FlatSharding* f, int32_t dtype, double p, uint64_t seed, uint64_t offset,
+                       const void* x, const void* residual, void* y, uint8_t* mask, int64_t i_begin, int64_t i_end,
+                       int threads, char* err, int errlen) {
+  return guarded(err, errlen, [&] {
+    const Sharding s = unflatten(f);
+    sliced(clip(s, i_begin, i_end), threads, [&](int64_t b, int64_t e) {
+      dropout_add(s, static_cast<DType>(dtype), p, seed, offset, b, e, x, residual, y, mask);
+    });
+  });
+}
+
 int oracle_randint(const FlatSharding* f, int64_t low, int64_t high, uint64_t seed, uint64_t offset,
                    int64_t* out, int64_t i_begin, int64_t i_end, int threads, char* err, int errlen) {
   return guarded(err, errlen, [&] {

@@ -169,6 +169,27 @@ void dropout(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offs
   });
 }
 
+void dropout_add(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offset, int64_t i_begin,
+                 int64_t i_end, const void* x, const void* residual, void* y, uint8_t* mask) {
+  const uint32_t threshold = dropout_threshold(p);
+  const float scale = dropout_scale(p);
+  for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
+    const uint32_t r = draw_at(s, seed, offset, j);
+    const bool keep = (r >> 8) < threshold;
+    if (mask) mask[i] = keep ? 1 : 0;
+    if (dt == kF32) {
+      const float prod = static_cast<const float*>(x)[i] * scale;
+      const float kept = keep ? prod : 0.0f;
+      static_cast<float*>(y)[i] = static_cast<const float*>(residual)[i] + kept;
+    } else {
+      const float prod = float_from_bf16(static_cast<const uint16_t*>(x)[i]) * scale;
+      const float kept = keep ? prod : 0.0f;
+      const float sum = float_from_bf16(static_cast<const uint16_t*>(residual)[i]) + kept;
+      static_cast<uint16_t*>(y)[i] = bf16_from_float(sum);
+    }
+  });
+}
+
 void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64_t offset,
              int64_t i_begin, int64_t i_end, int64_t* out) {
   const uint64_t range = static_cast<uint64_t>(high - low);

@@ -46,6 +46,9 @@ void normal_f64_values(const Sharding& s, double mean, double std, uint64_t seed
                        int64_t i_begin, int64_t i_end, double* out);
 void dropout(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offset,
              int64_t i_begin, int64_t i_end, const void* x, void* y, uint8_t* mask);
+// Dropout followed by a residual add: y = round_dtype(fl32(residual + (keep ? fl32(x * scale) : +0))).
+void dropout_add(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offset, int64_t i_begin,
+                 int64_t i_end, const void* x, const void* residual, void* y, uint8_t* mask);
 // Integers uniform in [low, high) (high - low <= 2^32): low + draw mod (high - low).
 void randint(const Sharding& s, int64_t low, int64_t high, uint64_t seed, uint64_t offset,
              int64_t i_begin, int64_t i_end, int64_t* out);

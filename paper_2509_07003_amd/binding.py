@@ -44,6 +44,7 @@ def _load():
         "vesrng_uniform": [sp, i32, dbl, dbl, u64, u64, vp, vp],
         "vesrng_normal": [sp, i32, dbl, dbl, u64, u64, vp, vp],
         "vesrng_dropout": [sp, i32, dbl, u64, u64, vp, vp, vp, vp],
+        "vesrng_dropout_add": [sp, i32, dbl, u64, u64, vp, vp, vp, vp, vp],
         "vesrng_randint": [sp, i64, i64, u64, u64, vp, vp],
     }
     for name, args in sigs.items():
@@ -168,6 +169,11 @@ def vesrng_normal(sharding, dtype, mean, std, seed, offset, out, stream=None):
 def vesrng_dropout(sharding, dtype, p, seed, offset, x, y, mask=None, stream=None):
     _check(_lib.vesrng_dropout(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(y), _dev(mask),
                                _stream(stream, x, y, mask)))
+
+
+def vesrng_dropout_add(sharding, dtype, p, seed, offset, x, residual, y, mask=None, stream=None):
+    _check(_lib.vesrng_dropout_add(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(residual), _dev(y),
+                                   _dev(mask), _stream(stream, x, residual, y, mask)))
 
 
 def vesrng_randint(sharding, low, high, seed, offset, out, stream=None):

@@ -168,6 +168,9 @@ __device__ __forceinline__ void convert_block(const uint32_t (&d)[4], const OpPa
   }
 }
 
+template <int OP>
+constexpr bool kIsDropout = (OP == kOpDropout || OP == kOpDropoutAdd);
+
 // OP: OpKind.  DT: output dtype.  A unit is what one thread stores: V elements.
 template <int OP, int DT>
 struct UnitOf {
@@ -179,7 +182,7 @@ struct UnitOf {
 // made by convert_block; dropout also consumes the 16 bytes of x loaded for the unit.
 template <int OP, int DT>
 __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kElems], const OpParams& prm,
-                                          u32x4 xv, uint64_t u, void* out, uint8_t* mask) {
+                                          u32x4 xv, u32x4 rv, uint64_t u, void* out, uint8_t* mask) {
   constexpr int NB = UnitOf<OP, DT>::kBlocks;
   if constexpr (OP == kOpRandint) {
     int64_t r[4];
@@ -191,7 +194,8 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
                       static_cast<uint32_t>(r[3]), static_cast<uint32_t>(static_cast<uint64_t>(r[3]) >> 32)};
     __builtin_nontemporal_store(lo, static_cast<u32x4*>(out) + 2 * u);
     __builtin_nontemporal_store(hi, static_cast<u32x4*>(out) + 2 * u + 1);
-  } else if constexpr (OP == kOpDropout) {
+  } else if constexpr (kIsDropout<OP>) {
+    constexpr bool kAdd = (OP == kOpDropoutAdd);
     u32x4 y;
     if constexpr (DT == kF32) {
       uint32_t m = 0;
@@ -199,7 +203,8 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
       for (int e = 0; e < 4; ++e) {
         const bool keep = keep_of(v[e], prm);
         const float prod = __fmul_rn(__uint_as_float(xv[e]), prm.scale);
-        y[e] = keep ? __float_as_uint(prod) : 0u;
+        const float kept = keep ? prod : 0.0f;
+        y[e] = __float_as_uint(kAdd ? __fadd_rn(__uint_as_float(rv[e]), kept) : kept);
         m |= (keep ? 1u : 0u) << (8 * e);
       }
       __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + u);
@@ -215,7 +220,12 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
           const float p0 = __fmul_rn(bf16_lo(pair), prm.scale);
           const float p1 = __fmul_rn(bf16_hi(pair), prm.scale);
           // Select before rounding: a dropped element becomes +0 whatever x held.
-          y[2 * b + h] = pack_bf16(k0 ? p0 : 0.0f, k1 ? p1 : 0.0f);
+          float y0 = k0 ? p0 : 0.0f, y1 = k1 ? p1 : 0.0f;
+          if constexpr (kAdd) {
+            y0 = __fadd_rn(bf16_lo(rv[2 * b + h]), y0);
+            y1 = __fadd_rn(bf16_hi(rv[2 * b + h]), y1);
+          }
+          y[2 * b + h] = pack_bf16(y0, y1);
           m[b] |= ((k0 ? 1u : 0u) | (k1 ? 0x100u : 0u)) << (16 * h);
         }
       }
@@ -246,15 +256,21 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
     static_cast<uint32_t*>(out)[i] = v;
   } else if constexpr (OP == kOpRandint) {
     static_cast<int64_t*>(out)[i] = randint_value(v, prm);
-  } else if constexpr (OP == kOpDropout) {
+  } else if constexpr (kIsDropout<OP>) {
+    constexpr bool kAdd = (OP == kOpDropoutAdd);
     const bool keep = keep_of(v, prm);
     if constexpr (DT == kF32) {
       const float x = static_cast<const float*>(xin)[i];
-      static_cast<float*>(out)[i] = keep ? __fmul_rn(x, prm.scale) : 0.0f;
+      const float kept = keep ? __fmul_rn(x, prm.scale) : 0.0f;
+      static_cast<float*>(out)[i] = kAdd ? __fadd_rn(static_cast<const float*>(prm.residual)[i], kept) : kept;
     } else {
       const uint32_t x = static_cast<const uint16_t*>(xin)[i];
-      const float prod = __fmul_rn(__uint_as_float(x << 16), prm.scale);
-      static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pack_bf16(keep ? prod : 0.0f, 0.0f));
+      float kept = keep ? __fmul_rn(__uint_as_float(x << 16), prm.scale) : 0.0f;
+      if constexpr (kAdd) {
+        const uint32_t r = static_cast<const uint16_t*>(prm.residual)[i];
+        kept = __fadd_rn(__uint_as_float(r << 16), kept);
+      }
+      static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pack_bf16(kept, 0.0f));
     }
     if (mask) mask[i] = keep ? 1 : 0;
   } else if constexpr (DT == kF32) {
@@ -331,8 +347,9 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   const uint64_t block0 = (run_pos + static_cast<uint64_t>(unit) * V) >> 2;
 
   // Dropout: issue the load before the generator so that it overlaps the ALU work.
-  u32x4 xv = {0u, 0u, 0u, 0u};
-  if constexpr (OP == kOpDropout) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + w64);
+  u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
+  if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + w64);
+  if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + w64);
 
   uint32_t d[NB][4];
 #pragma unroll
@@ -342,7 +359,8 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   // dependent rounds.
 #pragma unroll
   for (int b = 0; b < NB; ++b) asm volatile("" : "+v"(d[b][0]), "+v"(d[b][1]), "+v"(d[b][2]), "+v"(d[b][3]));
-  if constexpr (OP == kOpDropout) asm volatile("" : "+v"(xv));
+  if constexpr (kIsDropout<OP>) asm volatile("" : "+v"(xv));
+  if constexpr (OP == kOpDropoutAdd) asm volatile("" : "+v"(rv));
   if (!live) return;
 
   uint32_t v[V];
@@ -353,7 +371,7 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[4 * b + e] = vb[e];
   }
-  emit_unit<OP, DT>(v, prm, xv, w64, out, mask);
+  emit_unit<OP, DT>(v, prm, xv, rv, w64, out, mask);
 }
 
 // ---- tiled kernels ---------------------------------------------------------------
@@ -430,9 +448,10 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[4 * q + e] = t[e];
     }
-    u32x4 xv = {0u, 0u, 0u, 0u};
-    if constexpr (OP == kOpDropout) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
-    emit_unit<OP, DT>(v, prm, xv, u, out, mask);
+    u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
+    if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
+    if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + u);
+    emit_unit<OP, DT>(v, prm, xv, rv, u, out, mask);
   } else {
     // The last unit of a shard whose size is not a multiple of the unit.
     for (uint64_t i = e0; i < i1; ++i)
@@ -534,7 +553,7 @@ enum Flavour { kAligned, kTiled, kRagged };
 // (4.7 vs 4.1), but the uniform and normal fills spend too much arithmetic per element to
 // gain from it (4.0 vs 4.2 TB/s), so they keep the ragged kernel.
 template <int OP>
-constexpr bool kTileable = (OP == kOpRaw || OP == kOpRandint || OP == kOpDropout);
+constexpr bool kTileable = (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP>);
 
 template <int OP, int DT, typename IT, int NOUT>
 hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
@@ -639,6 +658,9 @@ hipError_t launch_op(OpKind op, const Geometry& g, uint64_t offset, const OpPara
     case kOpDropout:
       return bf16 ? launch_dt<kOpDropout, kBF16>(g, offset, prm, x, out, mask, stream)
                   : launch_dt<kOpDropout, kF32>(g, offset, prm, x, out, mask, stream);
+    case kOpDropoutAdd:
+      return bf16 ? launch_dt<kOpDropoutAdd, kBF16>(g, offset, prm, x, out, mask, stream)
+                  : launch_dt<kOpDropoutAdd, kF32>(g, offset, prm, x, out, mask, stream);
   }
   return hipErrorInvalidValue;
 }

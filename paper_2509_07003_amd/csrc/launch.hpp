@@ -8,7 +8,7 @@
 
 namespace vesrng {
 
-enum OpKind : int32_t { kOpRaw = 0, kOpUniform = 1, kOpNormal = 2, kOpDropout = 3, kOpRandint = 4 };
+enum OpKind : int32_t { kOpRaw = 0, kOpUniform = 1, kOpNormal = 2, kOpDropout = 3, kOpRandint = 4, kOpDropoutAdd = 5 };
 
 // Everything an operator needs besides the index plan; passed by value.
 struct OpParams {
@@ -24,6 +24,8 @@ struct OpParams {
   float scale = 1.f;
   uint32_t limit = 0;
   uint32_t keep_any = 1;
+  // dropout + residual: y = residual + dropout(x); device pointer, same shape and dtype as x
+  const void* residual = nullptr;
   // randint: out = base + draw mod range (range == 0 stands for 2^32)
   int64_t base = 0;
   uint32_t range = 0;

@@ -63,6 +63,29 @@ vesrng_status prepare(const vesrng_sharding* s, uint64_t seed, uint64_t offset, 
 
 vesrng_status finish(hipError_t e) { return e == hipSuccess ? VESRNG_OK : VESRNG_ERR_HIP; }
 
+vesrng_status dropout_common(OpKind op, const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
+                             uint64_t offset, const void* x, const void* residual, void* y, uint8_t* mask,
+                             void* hip_stream) {
+  Geometry g;
+  OpParams prm;
+  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
+  if (st != VESRNG_OK) return st;
+  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  if (!(p >= 0.0 && p <= 1.0)) return VESRNG_ERR_BAD_PARAM;
+  if (g.local_numel == 0) return VESRNG_OK;
+  if (!x || !y || (op == kOpDropoutAdd && !residual)) return VESRNG_ERR_NULL;
+  if (misaligned(x, 16) || misaligned(y, 16) || misaligned(mask, 16) || misaligned(residual, 16))
+    return VESRNG_ERR_ALIGN;
+  prm.dtype = dtype;
+  prm.residual = residual;
+  // keep = (draw >> 8) < T with T = round((1 - p) 2^24), i.e. draw <= (T << 8) - 1 for T >= 1.
+  const uint64_t threshold = static_cast<uint64_t>(std::floor((1.0 - p) * 16777216.0 + 0.5));
+  prm.keep_any = threshold != 0 ? 1u : 0u;
+  prm.limit = threshold != 0 ? static_cast<uint32_t>((threshold << 8) - 1) : 0u;
+  prm.scale = static_cast<float>(1.0 / (1.0 - p));
+  return finish(launch_op(op, g, offset, prm, x, y, mask, static_cast<hipStream_t>(hip_stream)));
+}
+
 }  // namespace
 
 extern "C" {
@@ -206,22 +229,13 @@ vesrng_status vesrng_normal(const vesrng_sharding* s, vesrng_dtype dtype, double
 
 vesrng_status vesrng_dropout(const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
                              uint64_t offset, const void* x, void* y, uint8_t* mask, void* hip_stream) {
-  Geometry g;
-  OpParams prm;
-  const vesrng_status st = prepare(s, seed, offset, &g, &prm);
-  if (st != VESRNG_OK) return st;
-  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
-  if (!(p >= 0.0 && p <= 1.0)) return VESRNG_ERR_BAD_PARAM;
-  if (g.local_numel == 0) return VESRNG_OK;
-  if (!x || !y) return VESRNG_ERR_NULL;
-  if (misaligned(x, 16) || misaligned(y, 16) || misaligned(mask, 16)) return VESRNG_ERR_ALIGN;
-  prm.dtype = dtype;
-  // keep = (draw >> 8) < T with T = round((1 - p) 2^24), i.e. draw <= (T << 8) - 1 for T >= 1.
-  const uint64_t threshold = static_cast<uint64_t>(std::floor((1.0 - p) * 16777216.0 + 0.5));
-  prm.keep_any = threshold != 0 ? 1u : 0u;
-  prm.limit = threshold != 0 ? static_cast<uint32_t>((threshold << 8) - 1) : 0u;
-  prm.scale = static_cast<float>(1.0 / (1.0 - p));
-  return finish(launch_op(kOpDropout, g, offset, prm, x, y, mask, static_cast<hipStream_t>(hip_stream)));
+  return dropout_common(kOpDropout, s, dtype, p, seed, offset, x, nullptr, y, mask, hip_stream);
+}
+
+vesrng_status vesrng_dropout_add(const vesrng_sharding* s, vesrng_dtype dtype, double p, uint64_t seed,
+                                 uint64_t offset, const void* x, const void* residual, void* y, uint8_t* mask,
+                                 void* hip_stream) {
+  return dropout_common(kOpDropoutAdd, s, dtype, p, seed, offset, x, residual, y, mask, hip_stream);
 }
 
 vesrng_status vesrng_randint(const vesrng_sharding* s, int64_t low, int64_t high, uint64_t seed,

@@ -528,3 +528,36 @@ def test_virtual_thread_layout(theta):
         single = out.cpu().numpy().view(np.uint32).reshape(shape)
         assert np.array_equal(merge_shards(shards, mesh, pls), single)
         assert v.vesrng_advance_offset(sh1, offset) == oracle.advance_offset(shape, offset, None, theta)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dropout_add_residual(dtype):
+    """Fused dropout + residual add, aligned / tiled / element-wise kernels, in place on either input."""
+    seed, offset = 2024, 128
+    code, ocode = (v.F32, oracle.F32) if dtype == "f32" else (v.BF16, oracle.BF16)
+    for args in (([64, 4096], [4], [("S", 0)], [3]),                               # aligned
+                 ([300, 333], [3], [("S", 1)], [1]),                               # ragged column shard (tiled)
+                 ([40, 7], [2], [("S", 1)], [1]),                                  # runs of 3: element-wise
+                 ([96], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1])):                # not a box
+        sh = v.Sharding(*args)
+        lshape, n = v.vesrng_local_shape(sh)
+        xf, rf = W.adversarial_f32(n, seed=1), W.adversarial_f32(n, seed=2)
+        x, r = (xf, rf) if dtype == "f32" else (W.bf16_bits_from_f32(xf), W.bf16_bits_from_f32(rf))
+        yo, mo = oracle.dropout_add(args, ocode, 0.1, seed, offset, x, r)
+
+        def dev(a):
+            return (torch.from_numpy(a).to(DEV) if dtype == "f32"
+                    else torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16))
+
+        def host(t):
+            return t.cpu().numpy() if dtype == "f32" else t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+        for alias in ("none", "x", "residual"):
+            xd, rd = dev(x), dev(r)
+            yd = {"none": torch.empty_like(xd), "x": xd, "residual": rd}[alias]
+            m = torch.empty(max(n, 1), dtype=torch.uint8, device=DEV)
+            v.vesrng_dropout_add(sh, code, 0.1, seed, offset, xd, rd, yd, m)
+            torch.cuda.synchronize()
+            what = "dropout_add %s %s alias=%s" % (dtype, args, alias)
+            assert np.array_equal(m.cpu().numpy()[:n].reshape(lshape), mo), what
+            assert_float_bits_equal(host(yd)[:n].reshape(lshape), yo, what)

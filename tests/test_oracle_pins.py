@@ -459,3 +459,22 @@ def test_virtual_thread_layout_keeps_the_merge_invariant_and_the_offset_rule():
     a = oracle.raw_u32(([6, 10], [1], [("R",)], [0], None, theta), seed, offset).reshape(-1)
     b = oracle.raw_u32(([6, 10], [1], [("R",)], [0], None, theta), seed, nxt).reshape(-1)
     assert not set(a.tolist()) & set(b.tolist())
+
+
+def test_dropout_add_is_dropout_then_an_fp32_add():
+    sh = ([6, 10], [2], [("S", 1)], [1])
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal(30).astype(np.float32)
+    r = rng.standard_normal(30).astype(np.float32)
+    y, m = oracle.dropout_add(sh, oracle.F32, 0.3, 4, 0, x, r)
+    yd, md = oracle.dropout(sh, oracle.F32, 0.3, 4, 0, x)
+    assert np.array_equal(m, md)
+    assert np.array_equal(y.reshape(-1), r + yd.reshape(-1))          # numpy fp32 add = one rounding
+    # bfloat16: product and sum are fp32, one rounding to bfloat16 at the end - torch's own ops agree.
+    xb = torch.from_numpy(x).to(torch.bfloat16)
+    rb = torch.from_numpy(r).to(torch.bfloat16)
+    y, m = oracle.dropout_add(sh, oracle.BF16, 0.3, 4, 0, xb.view(torch.int16).numpy().view(np.uint16),
+                              rb.view(torch.int16).numpy().view(np.uint16))
+    keep = torch.from_numpy(m.reshape(-1).astype(bool))
+    ref = (rb.float() + torch.where(keep, xb.float() * oracle.dropout_scale(0.3), torch.zeros(30))).to(torch.bfloat16)
+    assert np.array_equal(y.reshape(-1), ref.view(torch.int16).numpy().view(np.uint16))
