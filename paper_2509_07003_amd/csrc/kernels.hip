@@ -104,6 +104,8 @@ __device__ __forceinline__ float fraction24(uint32_t x) {
 }
 
 __device__ __forceinline__ float uniform_value(uint32_t x, const OpParams& prm) {
+  // [0, 1): u * 1 + 0 is u itself and never reaches 1 (wave-uniform branch).
+  if (prm.unit_range) return fraction24(x);
   const float scaled = __fmul_rn(fraction24(x), prm.width);
   const float r = __fadd_rn(scaled, prm.low);
   return r >= prm.high ? prm.top_f32 : r;
@@ -121,14 +123,12 @@ __device__ __forceinline__ uint32_t uniform_bf16_pack(float a, float b, const Op
 // their argument in revolutions, which is exactly u2).
 __device__ __forceinline__ void normal_pair(uint32_t xa, uint32_t xb, const OpParams& prm, float& even,
                                             float& odd) {
-  const float u1 = (static_cast<float>(xa >> 8) + 1.0f) * 0x1p-24f;  // (0, 1], exact
-  const float u2 = fraction24(xb);                                    // [0, 1), exact
+  const float u1 = __fmaf_rn(static_cast<float>(xa >> 8), 0x1p-24f, 0x1p-24f);  // ((xa >> 8) + 1) 2^-24, exact
+  const float u2 = fraction24(xb);                                               // [0, 1), exact
   const float r2 = __fmul_rn(__builtin_amdgcn_logf(u1), -1.3862943611198906f);  // -2 ln u1
-  const float radius = __builtin_amdgcn_sqrtf(r2);
-  const float c = __builtin_amdgcn_cosf(u2);
-  const float s = __builtin_amdgcn_sinf(u2);
-  even = __fmaf_rn(__fmul_rn(radius, c), prm.stddev, prm.mean);
-  odd = __fmaf_rn(__fmul_rn(radius, s), prm.stddev, prm.mean);
+  const float radius = __fmul_rn(__builtin_amdgcn_sqrtf(r2), prm.stddev);       // std * sqrt(-2 ln u1)
+  even = __fmaf_rn(radius, __builtin_amdgcn_cosf(u2), prm.mean);
+  odd = __fmaf_rn(radius, __builtin_amdgcn_sinf(u2), prm.mean);
 }
 
 __device__ __forceinline__ bool keep_of(uint32_t x, const OpParams& prm) {
@@ -282,6 +282,22 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
   }
 }
 
+// Makes the operator's scalar parameters live at the point of call, so that they are fetched
+// with the first batch of kernel arguments instead of in a second, dependent round after the
+// generator (the compiler otherwise loads them where the conversion first needs them).
+template <int OP>
+__device__ __forceinline__ void touch_params(const OpParams& prm) {
+  if constexpr (OP == kOpUniform)
+    asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.high), "s"(prm.top_f32), "s"(prm.top_bf16),
+                 "s"(prm.unit_range));
+  else if constexpr (OP == kOpNormal)
+    asm volatile("" ::"s"(prm.mean), "s"(prm.stddev));
+  else if constexpr (kIsDropout<OP>)
+    asm volatile("" ::"s"(prm.scale), "s"(prm.limit), "s"(prm.keep_any));
+  else if constexpr (OP == kOpRandint)
+    asm volatile("" ::"s"(prm.range), "s"(prm.range_m), "s"(prm.range_s));
+}
+
 // ---- locating work ---------------------------------------------------------------
 // Stream position of the first element of run `run`.  NOUT is the number of
 // run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
@@ -337,6 +353,8 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   constexpr int V = UnitOf<OP, DT>::kElems;
   // Threads past the end compute unit 0 again and skip the stores: no early exit, so all
   // kernel arguments are fetched in one batch at the top.
+  touch_params<OP>(prm);
+  asm volatile("" ::"s"(out), "s"(mask));
   const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   const bool live = t64 < plan.total_units;
   const uint64_t w64 = live ? t64 : 0;
@@ -350,6 +368,7 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
   if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + w64);
   if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + w64);
+  __builtin_amdgcn_sched_barrier(0);  // the loads are issued here, not moved down to their first use
 
   uint32_t d[NB][4];
 #pragma unroll
@@ -463,6 +482,7 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
 template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
+  touch_params<OP>(prm);
   const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   const bool in_range = t64 < plan.total_units;
   const IT w = in_range ? static_cast<IT>(t64) : 0;

@@ -199,6 +199,7 @@ vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, doubl
   prm.low = lo;
   prm.high = hi;
   prm.width = hi - lo;
+  prm.unit_range = (lo == 0.0f && hi == 1.0f) ? 1u : 0u;
   if (hi > lo) {
     prm.top_f32 = std::nextafterf(hi, lo);
     prm.top_bf16 = bf16_below(hi);
