@@ -561,3 +561,45 @@ def test_dropout_add_residual(dtype):
             what = "dropout_add %s %s alias=%s" % (dtype, args, alias)
             assert np.array_equal(m.cpu().numpy()[:n].reshape(lshape), mo), what
             assert_float_bits_equal(host(yd)[:n].reshape(lshape), yo, what)
+
+
+def test_random_descriptions_all_kernel_flavours():
+    """Seeded random meshes / placements / strides / layouts / offsets: raw draws, fp32 normals and
+    bf16 dropout against the oracle.  Exercises the choice between the aligned, tiled, ragged and
+    element-wise kernels and the 0 / 1 / many run-axis specialisations."""
+    from test_host_abi import _random_description
+    rng = np.random.default_rng(977)
+    done = 0
+    while done < 160:
+        shape, mesh, pls, coord, stride = _random_description(rng, max_extent=40)
+        theta = int(rng.choice([0, 0, 0, 3, 64]))
+        try:
+            n = oracle.local_shape(shape, mesh, pls, coord)[1]
+        except oracle.OracleError:
+            continue
+        if n == 0 or n > 400000:
+            continue
+        seed = int(rng.integers(0, 2 ** 63))
+        offset = 4 * int(rng.integers(0, 2 ** 40))
+        args = (shape, mesh, pls, coord, stride, theta)
+        what = str(args)
+        say(what)
+        sh = v.Sharding(*args)
+        lshape = v.vesrng_local_shape(sh)[0]
+        out = torch.empty(n, dtype=torch.int32, device=DEV)
+        v.vesrng_raw_u32(sh, seed, offset, out)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32).reshape(lshape), oracle.raw_u32(args, seed, offset)), what
+        o2 = torch.empty(n, dtype=torch.float32, device=DEV)
+        v.vesrng_normal(sh, v.F32, -1.0, 2.0, seed, offset, o2)
+        ref = oracle.normal_f64_values(args, -1.0, 2.0, seed, offset).reshape(-1)
+        err = np.abs(o2.cpu().numpy().astype(np.float64) - ref)
+        assert (err <= 1e-6 * np.maximum(np.abs(ref), 2.0)).all(), what
+        x = W.bf16_bits_from_f32(W.adversarial_f32(n, seed=done))
+        xd = torch.from_numpy(x.view(np.int16)).to(DEV).view(torch.bfloat16)
+        y = torch.empty_like(xd)
+        m = torch.empty(n, dtype=torch.uint8, device=DEV)
+        v.vesrng_dropout(sh, v.BF16, 0.15, seed, offset, xd, y, m)
+        yo, mo = oracle.dropout(args, oracle.BF16, 0.15, seed, offset, x)
+        assert np.array_equal(m.cpu().numpy().reshape(lshape), mo), what
+        assert_float_bits_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(lshape), yo, what)
+        done += 1

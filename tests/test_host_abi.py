@@ -191,3 +191,51 @@ def test_error_paths_return_their_status_without_touching_the_gpu():
     # Empty shard: fine, nothing to launch, pointers not needed.
     v.vesrng_uniform(v.Sharding([3, 5], [4], [("S", 0)], [3]), v.F32, 0.0, 1.0, 1, 0, None)
     v.vesrng_dropout(v.Sharding([0]), v.BF16, 0.1, 1, 0, None, None, None)
+
+
+def _random_description(rng, max_extent=9, allow_stride=True):
+    nd = int(rng.integers(1, 6))
+    shape = [int(x) for x in rng.integers(1, max_extent + 1, size=nd)]
+    md = int(rng.integers(1, 4))
+    mesh = [int(x) for x in rng.integers(1, 5, size=md)]
+    pls = []
+    for _ in range(md):
+        r = rng.random()
+        d = int(rng.integers(0, nd))
+        if r < 0.2:
+            pls.append(("R",))
+        elif r < 0.75:
+            pls.append(("S", d))
+        else:
+            pls.append(("IS", d, int(rng.integers(1, 5))))
+    coord = [int(rng.integers(0, p)) for p in mesh]
+    stride = None
+    if allow_stride and rng.random() < 0.3:
+        # A permuted, padded global layout: strides of a random dimension order with gaps.
+        order = list(rng.permutation(nd))
+        stride, acc = [0] * nd, 1
+        for d in order:
+            stride[d] = acc
+            acc *= shape[d] + int(rng.integers(0, 3))
+    return shape, mesh, pls, coord, stride
+
+
+def test_random_descriptions_against_the_oracle():
+    rng = np.random.default_rng(20240607)
+    ok = 0
+    for _ in range(1500):
+        shape, mesh, pls, coord, stride = _random_description(rng)
+        try:
+            want_shape, want_n = oracle.local_shape(shape, mesh, pls, coord)
+        except oracle.OracleError:
+            with pytest.raises(v.VesrngError):
+                v.vesrng_local_shape(v.Sharding(shape, mesh, pls, coord, stride))
+            continue
+        sh = v.Sharding(shape, mesh, pls, coord, stride)
+        assert v.vesrng_local_shape(sh) == (want_shape, want_n)
+        if want_n:
+            want_j = list(oracle.global_indices(shape, mesh, pls, coord, stride).reshape(-1))
+            assert v.vesrng_global_index(sh, range(want_n)) == want_j, (shape, mesh, pls, coord, stride)
+            assert v.vesrng_global_index_general(sh, range(want_n)) == want_j, (shape, mesh, pls, coord, stride)
+        ok += 1
+    assert ok > 1000

@@ -478,3 +478,10 @@ def test_dropout_add_is_dropout_then_an_fp32_add():
     keep = torch.from_numpy(m.reshape(-1).astype(bool))
     ref = (rb.float() + torch.where(keep, xb.float() * oracle.dropout_scale(0.3), torch.zeros(30))).to(torch.bfloat16)
     assert np.array_equal(y.reshape(-1), ref.view(torch.int16).numpy().view(np.uint16))
+
+
+def test_dropout_threshold_rounds_to_nearest():
+    # (1 - p) 2^24 = 9227468.8 for p = 0.45: nearest is ...469 (a floor would give ...468).
+    assert oracle.dropout_threshold(0.45) == 9227469
+    assert oracle.dropout_threshold(0.55) == 7549747      # 7549747.2 rounds down
+    assert oracle.dropout_threshold(2.0 ** -25) == 2 ** 24  # 2^24 - 0.5 rounds half up to 2^24: nothing is dropped
