@@ -103,6 +103,33 @@ def time_batch(torch, launch, reps, warmup):
     return a.elapsed_time(b) / reps
 
 
+VALU_PEAK = 256 * 4 * 32 * 2.4e9   # lane-operations/s: 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz
+                                   # (= the published 157.3 TFLOP/s fp32 vector rate / 2 flops per FMA)
+
+
+def steady_state(v, W, torch):
+    """The kernels of the small configs at 64x the shard (same shapes of run, same kernel), where
+    launch latency no longer dominates: C2's ragged fp32 normal fill and C3's bf16 normal fill.
+    The bf16 fill is ALU-bound; its roofline is the vector issue rate (VALU instructions per
+    element from profiles/counters_bench_kernels.txt)."""
+    import copy
+    res = {}
+    for wl, scale_dim, valu_per_elem in ((W.C2, 0, 99.7 / 4), (W.C3, 0, 161.0 / 8)):
+        big = copy.deepcopy(wl)
+        big.global_shape = list(wl.global_shape)
+        big.global_shape[scale_dim] *= 64
+        launch, numel, nb = make_launcher(v, W, torch, big, wl.bench_coord, 1)
+        avg, med, mn = time_kernel(torch, launch, 20, 3)
+        gbs = nb / (med * 1e-3) / 1e9
+        lane_ops = valu_per_elem * numel / (med * 1e-3)
+        res[wl.name.split()[0] + "x64"] = {
+            "workload": "%s with dim %d x64 (beyond the 256 MB last-level cache): shard of %d elements" % (wl.name, scale_dim, numel),
+            "median_launch_us": med * 1e3, "gb_per_s": gbs, "pct_hbm_peak": 100 * gbs / HBM_PEAK_GBS,
+            "gsamples_per_s": numel / (med * 1e-3) / 1e9,
+            "valu_lane_ops_per_s": lane_ops, "pct_valu_issue_peak": 100 * lane_ops / VALU_PEAK}
+    return res
+
+
 def cpu_baseline(torch, W, w, coord, x_dev, sample):
     """The oracle, as it stands, on the first `sample` elements of the same shard."""
     import numpy as np
@@ -167,7 +194,7 @@ def main():
     # Dominant (only) kernel of the step, timed with events on the launch stream.
     avg_ms, med_ms, min_ms = time_kernel(torch, step, a.steps, 2)
     achieved = nbytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "aligned_kernel<dropout,bf16>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+    roofline = {"bound": "hbm", "kernel": "vesrng::aligned_kernel<3 (dropout), 1 (bf16), unsigned int, 1 run axis>", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("c5_dropout_bf16"),
                 "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms,
                 "algorithmic_bytes_per_launch": nbytes}
@@ -200,6 +227,7 @@ def main():
                 "pct_hbm_peak": 100 * nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_cycled": copies,
                 "note": "back-to-back launches incl. host call overhead; buffers cycled to exceed the last-level cache"}
         out["per_config"] = extra
+        out["steady_state"] = steady_state(v, W, torch)
     print(json.dumps(out), flush=True)
 
 
