@@ -9,15 +9,20 @@
 //  * aligned kernels: every run of the shard starts on a block boundary and its
 //    length is a multiple of the unit (4 or 8 elements); unit w covers local
 //    elements [w*V, (w+1)*V) and all accesses are 16-byte vectors.
-//  * tiled kernels: any run start / length (e.g. a column shard whose first
-//    column is 1366).  A workgroup owns a 16-byte aligned tile of the LOCAL
-//    tensor; its threads first own the GLOBAL blocks that intersect the tile and
-//    scatter their values into LDS at local positions, then each thread takes an
-//    aligned unit back out of LDS and stores it.  One block still feeds four
-//    outputs, and every global access is an aligned 128-bit vector: 16-byte
-//    stores that are only 4- or 8-byte aligned run at 4.9 instead of 6.8 TB/s.
-//  * ragged kernels: the element-wise general path (runs shorter than 16
-//    elements, innermost global stride other than 1).
+//  * ragged kernels: any run start / length (e.g. a column shard whose first
+//    column is 1366).  A thread owns one GLOBAL block and stores the lanes that
+//    fall inside the run; whole blocks leave as one element-aligned vector store.
+//    Used by the uniform and normal fills, and wherever runs are shorter than 16
+//    elements or the innermost global stride is not 1.
+//  * tiled kernels: ragged shards of the raw, randint and dropout operators.  A
+//    workgroup owns a 128-byte aligned tile of the LOCAL tensor; its threads first
+//    own the GLOBAL blocks that intersect the tile and scatter their values into
+//    LDS at local positions, then each thread takes an aligned unit back out of
+//    LDS and stores it.  One block still feeds four outputs, and every global
+//    access is an aligned 128-bit vector (wave stores that do not cover whole
+//    128-byte lines run at 4.9 instead of 6.8 TB/s).
+//  * chain kernel: Algorithm 1 element by element, for shards that are not boxes
+//    and for the virtual-thread layout.
 //
 // Launches are one-shot (one unit per thread): on MI355X this sustained a higher
 // rate than grid-stride loops or several units per thread.
