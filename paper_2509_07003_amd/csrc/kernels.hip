@@ -28,6 +28,10 @@
 // rate than grid-stride loops or several units per thread.
 #include <hip/hip_runtime.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "launch.hpp"
 #include "plan.h"
 
@@ -526,6 +530,11 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
       emit_element<OP, DT>(v[e], prm, xin, li0 + e, out, mask);
 }
 
+template <typename Tuple, size_t... I>
+void fill_pointers(Tuple& values, void** ptrs, std::index_sequence<I...>) {
+  ((ptrs[I] = &std::get<I>(values)), ...);
+}
+
 // ---- chain kernel: Algorithm 1 element by element ----------------------------------
 // For shards that are not boxes, and for the virtual-thread layout.  One thread per local
 // element: decode, map every coordinate back through the placements, one generator block
@@ -560,15 +569,25 @@ chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, co
   emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
 }
 
+// Enqueues `kernel` and returns the launch's own status (hipGetLastError would also report,
+// and clear, an error some other code left behind).
+template <typename... Params, typename... Args>
+hipError_t enqueue(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+  static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+  std::tuple<std::remove_cv_t<Params>...> values{args...};
+  void* ptrs[sizeof...(Params)];
+  fill_pointers(values, ptrs, std::index_sequence_for<Params...>{});
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+}
+
 template <int OP, int DT>
 hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                         uint8_t* mask, hipStream_t stream) {
   const uint64_t n = static_cast<uint64_t>(g.local_numel);
   const uint64_t blocks = (n + kThreads - 1) / kThreads;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  hipLaunchKernelGGL((chain_kernel<OP, DT>), dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream,
-                     g.chain, offset, g.virtual_threads, n, prm, x, out, mask);
-  return hipGetLastError();
+  return enqueue(chain_kernel<OP, DT>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), stream, g.chain, offset,
+                 g.virtual_threads, n, prm, x, out, mask);
 }
 
 // ---- dispatch --------------------------------------------------------------------
@@ -594,21 +613,17 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
   switch (flavour) {
     case kAligned:
-      hipLaunchKernelGGL((aligned_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
-      break;
+      return enqueue(aligned_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
       if constexpr (kTileable<OP>)
-        hipLaunchKernelGGL((tiled_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm,
-                           (TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}),
-                           x, out, mask);
-      else
-        return hipErrorInvalidValue;
+        return enqueue(tiled_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm,
+                       TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
+                       mask);
       break;
     case kRagged:
-      hipLaunchKernelGGL((ragged_kernel<OP, DT, IT, NOUT>), grid, block, 0, stream, plan, prm, x, out, mask);
-      break;
+      return enqueue(ragged_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);
   }
-  return hipGetLastError();
+  return hipErrorInvalidValue;
 }
 
 template <int OP, int DT, typename IT>
