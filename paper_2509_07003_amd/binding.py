@@ -112,11 +112,21 @@ def _dev(buf):
     return C.c_void_p(buf.data_ptr())
 
 
+def _current_stream(device_index):
+    """torch's current stream on the device as a raw hipStream_t (the private accessor is several
+    times cheaper than torch.cuda.current_stream(), which matters for microsecond kernels)."""
+    import torch
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is not None:
+        return raw(device_index if device_index is not None else torch.cuda.current_device())
+    return torch.cuda.current_stream(device_index).cuda_stream
+
+
 def _stream(stream, *bufs):
     if stream is None:
-        if any(b is not None and not isinstance(b, int) for b in bufs):
-            import torch
-            return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for b in bufs:
+            if b is not None and not isinstance(b, int):
+                return C.c_void_p(_current_stream(b.device.index))
         return None
     if isinstance(stream, int):
         return C.c_void_p(stream)

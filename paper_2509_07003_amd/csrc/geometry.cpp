@@ -17,7 +17,7 @@ struct Sub {
   int64_t step;
 };
 struct DimBox {
-  std::vector<Sub> subs;  // outermost first
+  SmallVec<Sub, kMaxSubs> subs;  // outermost first
   int64_t origin = 0;
   int64_t length() const {
     int64_t n = 1;
@@ -84,7 +84,8 @@ vesrng_status apply_interleaved(DimBox& box, int64_t groups, int64_t parts, int6
       const int64_t per = e / remaining;
       const int64_t step = box.subs[k].step;
       box.subs[k] = Sub{remaining, step * per};
-      box.subs.insert(box.subs.begin() + static_cast<long>(k) + 1, Sub{per, step});
+      if (box.subs.full()) return VESRNG_ERR_UNSUPPORTED;
+      box.subs.insert_at(k + 1, Sub{per, step});
       remaining = 1;
       ++k;
     } else if (remaining % e == 0) {
@@ -94,7 +95,10 @@ vesrng_status apply_interleaved(DimBox& box, int64_t groups, int64_t parts, int6
       return VESRNG_ERR_UNSUPPORTED;
     }
   }
-  if (k == box.subs.size()) box.subs.push_back(Sub{1, 1});  // groups of one entry
+  if (k == box.subs.size()) {
+    if (box.subs.full()) return VESRNG_ERR_UNSUPPORTED;
+    box.subs.push_back(Sub{1, 1});  // groups of one entry
+  }
   int64_t start, len;
   chunk_range(n / groups, parts, which, &start, &len);
   if (len == 0) {
@@ -131,7 +135,8 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
     numel = 0;
 
   // Global strides (Algorithm 1's pi) and the largest flat index they reach.
-  std::vector<int64_t> pi(static_cast<size_t>(nd), 1);
+  SmallVec<int64_t, kMaxDims> pi;
+  pi.assign(static_cast<size_t>(nd), 1);
   if (s->global_stride) {
     for (int d = 0; d < nd; ++d) {
       if (s->global_stride[d] <= 0) return VESRNG_ERR_OVERFLOW;
@@ -167,8 +172,10 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
 
   // Two descriptions are built side by side: the chain of placements per dimension (always
   // possible) and the box form the fast kernels need (dropped as soon as a cut has no box).
-  std::vector<DimBox> boxes(static_cast<size_t>(nd));
-  std::vector<int64_t> length(static_cast<size_t>(nd));
+  SmallVec<DimBox, kMaxDims> boxes;
+  boxes.assign(static_cast<size_t>(nd), DimBox{});
+  SmallVec<int64_t, kMaxDims> length;
+  length.assign(static_cast<size_t>(nd), 0);
   for (int d = 0; d < nd; ++d) {
     boxes[static_cast<size_t>(d)].subs.assign(1, Sub{s->global_shape[d], 1});
     length[static_cast<size_t>(d)] = s->global_shape[d];
@@ -218,7 +225,7 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
   g->axes.clear();
   if (g->local_numel == 0 || !g->boxed) return VESRNG_OK;
 
-  std::vector<Axis> raw;
+  SmallVec<Axis, kMaxAxes> raw;
   for (int d = 0; d < nd; ++d) {
     const DimBox& box = boxes[static_cast<size_t>(d)];
     const int64_t st = pi[static_cast<size_t>(d)];

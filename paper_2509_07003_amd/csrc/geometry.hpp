@@ -2,13 +2,43 @@
 // turns it into closed-form shard geometry (veScale Section 2.2: device mesh,
 // placements, local tensor; Algorithm 1's metadata upsilon, omega, pi, rho).
 #pragma once
+#include <cstddef>
 #include <cstdint>
-#include <vector>
 
 #include "../../include/vesrng.h"
 #include "plan.h"
 
 namespace vesrng {
+
+// A vector with inline storage: shard descriptions are tiny (at most 8 dimensions, a few axes
+// each) and are rebuilt on every call, so nothing here touches the heap.
+template <typename T, int N>
+struct SmallVec {
+  T item[N];
+  int count = 0;
+  size_t size() const { return static_cast<size_t>(count); }
+  bool empty() const { return count == 0; }
+  bool full() const { return count == N; }
+  void clear() { count = 0; }
+  T& operator[](size_t k) { return item[k]; }
+  const T& operator[](size_t k) const { return item[k]; }
+  T& back() { return item[count - 1]; }
+  const T& back() const { return item[count - 1]; }
+  const T* begin() const { return item; }
+  const T* end() const { return item + count; }
+  void push_back(const T& v) { item[count++] = v; }
+  void assign(size_t n, const T& v) {
+    count = static_cast<int>(n);
+    for (int k = 0; k < count; ++k) item[k] = v;
+  }
+  void insert_at(size_t pos, const T& v) {
+    for (size_t k = static_cast<size_t>(count); k > pos; --k) item[k] = item[k - 1];
+    item[pos] = v;
+    ++count;
+  }
+};
+constexpr int kMaxSubs = 12;                    // axes of one tensor dimension
+constexpr int kMaxAxes = kMaxDims * kMaxSubs;   // axes of a whole shard before merging
 
 // One axis of the shard seen as a box in the flattened global tensor.
 struct Axis {
@@ -17,12 +47,12 @@ struct Axis {
 };
 
 struct Geometry {
-  std::vector<int64_t> local_shape;  // per tensor dimension
+  SmallVec<int64_t, kMaxDims> local_shape;  // per tensor dimension
   int64_t local_numel = 0;
   uint64_t global_numel = 0;         // product of the global shape
   uint64_t max_global_index = 0;     // largest global flat index of the whole tensor
   uint64_t origin = 0;               // global flat index of local element 0
-  std::vector<Axis> axes;            // outermost first; local tensor is row-major over them,
+  SmallVec<Axis, kMaxAxes> axes;     // outermost first; local tensor is row-major over them,
                                      // extent-1 axes dropped, mergeable neighbours merged
   uint64_t virtual_threads = 0;      // Algorithm 1's global thread count Theta; 0 = flat stream
   bool boxed = true;                 // false: the shard is not a box; only `chain` describes it
@@ -35,7 +65,7 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g);
 // Shape of the work a kernel launch covers.
 struct RunShape {
   uint64_t run_len = 1;              // innermost axis if its global stride is 1, else 1
-  std::vector<Axis> outer;           // innermost outer axis first
+  SmallVec<Axis, kMaxAxes> outer;    // innermost outer axis first
   uint64_t n_runs = 1;
   bool phases_equal = true;          // every run starts at the same position modulo 4
 };
