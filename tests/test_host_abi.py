@@ -239,3 +239,34 @@ def test_random_descriptions_against_the_oracle():
             assert v.vesrng_global_index_general(sh, range(want_n)) == want_j, (shape, mesh, pls, coord, stride)
         ok += 1
     assert ok > 1000
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and a C program can call the
+    host-only entry points of the shared library."""
+    import subprocess
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "vesrng.h"
+int main(void) {
+  int64_t shape[2] = {4096, 4096};
+  int32_t mesh[1] = {3}, coord[1] = {2};
+  vesrng_placement pl[1] = {{VESRNG_SHARD, 1, 0}};
+  vesrng_sharding s = {2, shape, 0, 1, mesh, pl, coord, 0};
+  int64_t local[2], n;
+  uint64_t next;
+  if (vesrng_local_shape(&s, local, &n) != VESRNG_OK) return 1;
+  if (vesrng_advance_offset(&s, 0, &next) != VESRNG_OK) return 2;
+  printf("%lld %lld %lld %llu %s\n", (long long)local[0], (long long)local[1], (long long)n,
+         (unsigned long long)next, vesrng_status_string(VESRNG_ERR_OFFSET_ALIGN));
+  return vesrng_uniform(&s, VESRNG_F32, 0.0, 1.0, 1, 2, (void*)16, 0) == VESRNG_ERR_OFFSET_ALIGN ? 0 : 3;
+}
+''')
+    exe = tmp_path / "abi"
+    lib = v.library_path()
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), lib, "-Wl,-rpath," + os.path.dirname(lib)], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout.split(None, 4)
+    assert out[:4] == ["4096", "1364", str(4096 * 1364), "16777216"]
+    assert "multiple of 4" in out[4]
