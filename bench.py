@@ -103,6 +103,30 @@ def time_batch(torch, launch, reps, warmup):
     return a.elapsed_time(b) / reps
 
 
+def measured_ceilings(v, torch):
+    """Rates of the plain probe kernels on this machine, in this run: what bare 128-bit stores,
+    a 16-byte copy, the dropout kernel's access pattern without arithmetic, and the generator
+    alone can reach.  1 GiB buffers (beyond the 256 MB last-level cache)."""
+    nbytes = 1 << 30
+    units = nbytes // 16
+    a = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    m = torch.empty(nbytes // 8, dtype=torch.int32, device="cuda")
+    blocks = 1 << 30
+
+    def med(fn):
+        return time_kernel(torch, lambda _k: fn(), 20, 3)[1] * 1e-3
+
+    t_store = med(lambda: v.vesrng_probe(v.PROBE_STORE, units, None, a))
+    t_copy = med(lambda: v.vesrng_probe(v.PROBE_COPY, units, a, b))
+    t_mix = med(lambda: v.vesrng_probe(v.PROBE_DROPOUT_TRAFFIC, units, a, b, m))
+    t_gen = med(lambda: v.vesrng_probe(v.PROBE_PHILOX, blocks, None, a))
+    return {"store_only_gb_per_s": nbytes / t_store / 1e9, "copy_gb_per_s": 2 * nbytes / t_copy / 1e9,
+            "dropout_traffic_gb_per_s": 2.5 * nbytes / t_mix / 1e9,
+            "philox_only_gblocks_per_s": blocks / t_gen / 1e9,
+            "note": "plain probe kernels of the library (vesrng_probe), medians of 20 launches in this run"}
+
+
 VALU_PEAK = 256 * 4 * 32 * 2.4e9   # lane-operations/s: 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz
                                    # (= the published 157.3 TFLOP/s fp32 vector rate / 2 flops per FMA)
 
@@ -217,6 +241,10 @@ def main():
 
     if not a.no_extra:
         del x, y, mask
+        ceil = measured_ceilings(v, torch)
+        out["ceilings"] = ceil
+        roofline["frac_of_measured_traffic_ceiling"] = achieved / ceil["dropout_traffic_gb_per_s"]
+        roofline["frac_of_measured_generator_ceiling"] = (n / 4 / (avg_ms * 1e-3) / 1e9) / ceil["philox_only_gblocks_per_s"]
         extra = {}
         for wl, copies in ((W.C1, 256), (W.C2, 16), (W.C3, 32), (W.C4, 8), (W.C5_INTERLEAVED, 1)):
             launch, numel, nb = make_launcher(v, W, torch, wl, wl.bench_coord, copies)
@@ -228,6 +256,9 @@ def main():
                 "note": "back-to-back launches incl. host call overhead; buffers cycled to exceed the last-level cache"}
         out["per_config"] = extra
         out["steady_state"] = steady_state(v, W, torch)
+        for r in out["steady_state"].values():
+            r["pct_of_measured_store_ceiling"] = 100 * r["gb_per_s"] / ceil["store_only_gb_per_s"]
+            r["pct_of_measured_generator_ceiling"] = 100 * (r["gsamples_per_s"] / 4) / ceil["philox_only_gblocks_per_s"]
     print(json.dumps(out), flush=True)
 
 

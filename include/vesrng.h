@@ -167,6 +167,21 @@ VESRNG_API vesrng_status vesrng_dropout_add(const vesrng_sharding* s, vesrng_dty
 VESRNG_API vesrng_status vesrng_randint(const vesrng_sharding* s, int64_t low, int64_t high, uint64_t seed,
                              uint64_t offset, int64_t* out, void* hip_stream);
 
+/* Measurement aid, not part of the method: plain kernels whose rates bound the real ones.
+ * `units` 16-byte units are touched (STORE: written to out; COPY: in -> out; DROPOUT_TRAFFIC:
+ * 16 bytes in, 16 bytes to out and 8 bytes to out2 per unit, the bf16 dropout kernel's accesses
+ * without its arithmetic), or `units` Philox4x32-10 blocks are generated and discarded (PHILOX;
+ * out must still be a valid device pointer of at least 1 KiB).  Device pointers, 16-byte aligned;
+ * asynchronous on hip_stream. */
+typedef enum {
+  VESRNG_PROBE_STORE = 0,
+  VESRNG_PROBE_COPY = 1,
+  VESRNG_PROBE_DROPOUT_TRAFFIC = 2,
+  VESRNG_PROBE_PHILOX = 3
+} vesrng_probe_kind;
+VESRNG_API vesrng_status vesrng_probe(vesrng_probe_kind kind, uint64_t units, const void* in, void* out,
+                                      void* out2, void* hip_stream);
+
 VESRNG_API const char* vesrng_status_string(vesrng_status st);
 
 #ifdef __cplusplus

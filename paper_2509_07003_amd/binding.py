@@ -46,6 +46,7 @@ def _load():
         "vesrng_dropout": [sp, i32, dbl, u64, u64, vp, vp, vp, vp],
         "vesrng_dropout_add": [sp, i32, dbl, u64, u64, vp, vp, vp, vp, vp],
         "vesrng_randint": [sp, i64, i64, u64, u64, vp, vp],
+        "vesrng_probe": [i32, u64, vp, vp, vp, vp],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -184,6 +185,13 @@ def vesrng_dropout(sharding, dtype, p, seed, offset, x, y, mask=None, stream=Non
 def vesrng_dropout_add(sharding, dtype, p, seed, offset, x, residual, y, mask=None, stream=None):
     _check(_lib.vesrng_dropout_add(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(residual), _dev(y),
                                    _dev(mask), _stream(stream, x, residual, y, mask)))
+
+
+PROBE_STORE, PROBE_COPY, PROBE_DROPOUT_TRAFFIC, PROBE_PHILOX = 0, 1, 2, 3
+
+
+def vesrng_probe(kind, units, src, out, out2=None, stream=None):
+    _check(_lib.vesrng_probe(kind, units, _dev(src), _dev(out), _dev(out2), _stream(stream, src, out, out2)))
 
 
 def vesrng_randint(sharding, low, high, seed, offset, out, stream=None):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvesrng.so")
-SOURCES = ["kernels.hip", "geometry.cpp", "vesrng.cpp"]
+SOURCES = ["kernels.hip", "probes.hip", "geometry.cpp", "vesrng.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -ffp-contract=off: every fp32 operation in the value definitions rounds on its own

@@ -33,6 +33,7 @@
 #include <utility>
 
 #include "launch.hpp"
+#include "philox.h"
 #include "plan.h"
 
 namespace vesrng {
@@ -65,40 +66,6 @@ template <>
 struct SignedOf<uint64_t> {
   using type = int64_t;
 };
-
-// ---- generator ---------------------------------------------------------------
-// a ^ b ^ c in one instruction (v_bitop3_b32, truth table 0x96); the compiler emits two
-// v_xor_b32 for the plain expression, and the XORs are half of Philox's instructions.
-__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
-  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
-}
-
-// Philox4x32-10 on counter (c0, c1, c2, c3), key (k0, k1).
-__device__ __forceinline__ void philox_rounds(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                              uint32_t k1, uint32_t (&w)[4]) {
-#pragma unroll
-  for (int round = 0; round < 10; ++round) {
-    const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
-    const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-    const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
-    const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
-    c1 = static_cast<uint32_t>(p1);
-    c3 = static_cast<uint32_t>(p0);
-    c0 = n0;
-    c2 = n2;
-    k0 += 0x9E3779B9u;  // wave-uniform: lives in scalar registers
-    k1 += 0xBB67AE85u;
-  }
-  w[0] = c0;
-  w[1] = c1;
-  w[2] = c2;
-  w[3] = c3;
-}
-
-// Block b of the flat stream: counter (lo32 b, hi32 b, 0, 0).
-__device__ __forceinline__ void philox_block(uint64_t b, uint32_t k0, uint32_t k1, uint32_t (&w)[4]) {
-  philox_rounds(static_cast<uint32_t>(b), static_cast<uint32_t>(b >> 32), 0u, 0u, k0, k1, w);
-}
 
 // ---- conversions ---------------------------------------------------------------
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {

@@ -603,3 +603,22 @@ def test_random_descriptions_all_kernel_flavours():
         assert np.array_equal(m.cpu().numpy().reshape(lshape), mo), what
         assert_float_bits_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(lshape), yo, what)
         done += 1
+
+
+def test_ceiling_probes_do_what_they_say():
+    """The measurement aids: store pattern, copy, dropout traffic pattern, generator-only."""
+    units = 4096 + 3
+    a = torch.zeros(units * 4, dtype=torch.int32, device=DEV)
+    v.vesrng_probe(v.PROBE_STORE, units, None, a)
+    torch.cuda.synchronize()
+    got = a.cpu().numpy().reshape(units, 4)
+    assert np.array_equal(got, np.arange(units, dtype=np.int32)[:, None] + np.arange(4, dtype=np.int32)[None, :])
+    b = torch.zeros_like(a)
+    v.vesrng_probe(v.PROBE_COPY, units, a, b)
+    m = torch.zeros(units * 2, dtype=torch.int32, device=DEV)
+    c = torch.zeros_like(a)
+    v.vesrng_probe(v.PROBE_DROPOUT_TRAFFIC, units, a, c, m)
+    v.vesrng_probe(v.PROBE_PHILOX, 1 << 20, None, b)     # generates and discards: b must stay a copy of a
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(a, c)
+    assert np.array_equal(m.cpu().numpy().reshape(units, 2), got[:, :2] & 0x01010101)

@@ -188,6 +188,11 @@ def test_error_paths_return_their_status_without_touching_the_gpu():
     assert _status(v.vesrng_randint, ok, 0, (1 << 32) + 1, 1, 0, buf) == 7
     assert _status(v.vesrng_raw_u32, ok, 1, 0, None) == 1
     assert _status(v.vesrng_raw_u32, v.Sharding([4], [2], [("P",)], [0]), 1, 0, buf) == 5
+    assert _status(v.vesrng_probe, v.PROBE_COPY, 16, None, buf) == 1
+    assert _status(v.vesrng_probe, v.PROBE_DROPOUT_TRAFFIC, 16, buf, buf, None) == 1
+    assert _status(v.vesrng_probe, v.PROBE_STORE, 16, None, buf + 8) == 12
+    assert _status(v.vesrng_probe, 9, 16, buf, buf, buf) == 7
+    v.vesrng_probe(v.PROBE_STORE, 0, None, None)
     # Empty shard: fine, nothing to launch, pointers not needed.
     v.vesrng_uniform(v.Sharding([3, 5], [4], [("S", 0)], [3]), v.F32, 0.0, 1.0, 1, 0, None)
     v.vesrng_dropout(v.Sharding([0]), v.BF16, 0.1, 1, 0, None, None, None)
