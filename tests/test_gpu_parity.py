@@ -210,19 +210,15 @@ def _c5_check(w, coord):
     xh = x.view(torch.int16).cpu().numpy().view(np.uint16)
     yh = y.view(torch.int16).cpu().numpy().view(np.uint16)
     mh = mask.cpu().numpy()
-    # Whole-shard properties, then element-by-element parity on sampled ranges that
-    # include both ends and the seams between the non-contiguous slabs.
+    # Whole-shard properties, then element-by-element parity over the WHOLE shard (the threaded
+    # oracle does 2^29 elements in about a second).
     assert abs(mh.mean() - 0.899999976) < 5.2e-5
     assert not yh[mh == 0].any()
-    slab = n // 8
-    ranges = [(0, 1 << 20), (n - (1 << 20), n)]
-    ranges += [(k * slab - (1 << 18), k * slab + (1 << 18)) for k in (1, 4, 7)]
-    ranges += [((1 << 24) * 5 - 4096, (1 << 24) * 5 + 4096), (n // 3, n // 3 + (1 << 20))]
-    for b, e in ranges:
-        say("  oracle on [%d, %d)" % (b, e))
-        yo, mo = oracle.dropout(tuple(args), oracle.BF16, 0.1, w.seed, 0, xh, i_begin=b, i_end=e, threads=THREADS)
-        assert np.array_equal(mh[b:e], mo.reshape(-1)[b:e])
-        assert_float_bits_equal(yh[b:e], yo.reshape(-1)[b:e], "%s [%d,%d)" % (w.name, b, e))
+    say("  oracle on all %d elements" % n)
+    yo, mo = oracle.dropout(tuple(args), oracle.BF16, 0.1, w.seed, 0, xh, threads=THREADS)
+    assert np.array_equal(mh, mo.reshape(-1))
+    del mo
+    assert_float_bits_equal(yh, yo.reshape(-1), w.name)
 
 
 def test_c5_dropout_bf16_attention_probabilities_nested_shard_full_size():
