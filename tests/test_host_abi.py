@@ -275,3 +275,20 @@ int main(void) {
     out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout.split(None, 4)
     assert out[:4] == ["4096", "1364", str(4096 * 1364), "16777216"]
     assert "multiple of 4" in out[4]
+
+
+def test_import_fails_loudly_without_the_native_library(tmp_path):
+    """No CPU fallback: a copy of the package without libvesrng.so and without a working hipcc
+    must refuse to import rather than compute anything some other way."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2509_07003_amd"
+    pkg.mkdir()
+    for name in ("__init__.py", "binding.py", "build.py", "workloads.py"):
+        shutil.copy(os.path.join(ROOT, "paper_2509_07003_amd", name), pkg / name)
+    env = dict(os.environ, HIPCC="/bin/false", PYTHONPATH=str(tmp_path))
+    res = subprocess.run([sys.executable, "-c", "import paper_2509_07003_amd"], env=env, cwd=str(tmp_path),
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert res.returncode != 0
+    assert "hipcc failed" in res.stderr or "libvesrng" in res.stderr
