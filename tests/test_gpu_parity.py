@@ -618,3 +618,51 @@ def test_ceiling_probes_do_what_they_say():
     torch.cuda.synchronize()
     assert torch.equal(a, b) and torch.equal(a, c)
     assert np.array_equal(m.cpu().numpy().reshape(units, 2), got[:, :2] & 0x01010101)
+
+
+def test_in_place_dropout_on_ragged_and_non_box_shards():
+    for args in (([300, 333], [3], [("S", 1)], [1]), ([40, 7], [2], [("S", 1)], [1]),
+                 ([96], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1]), ([5, 9, 11], [2, 2], [("S", 2), ("S", 0)], [1, 0])):
+        n = oracle.local_shape(*args)[1]
+        for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16)):
+            xf = W.adversarial_f32(n, seed=7)
+            x = xf if dtype == "f32" else W.bf16_bits_from_f32(xf)
+            yo, mo = oracle.dropout(args, code, 0.35, 12, 64, x)
+            y, m = gpu_dropout(dtype, args, 0.35, 12, 64, x, with_mask=True, in_place=True)
+            assert np.array_equal(m, mo), (args, dtype)
+            assert_float_bits_equal(y, yo, "in-place dropout %s %s" % (dtype, args))
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """The entry points only enqueue kernels (no allocation, no synchronisation, no memset), so a
+    caller can capture them; every replay must reproduce the eager result."""
+    args = ([64, 1030], [3], [("S", 1)], [1])            # ragged: tiled dropout + ragged normal
+    sh = v.Sharding(*args)
+    lshape, n = v.vesrng_local_shape(sh)
+    x_bits = W.bf16_bits_from_f32(np.random.default_rng(3).standard_normal(n).astype(np.float32))
+    x = torch.from_numpy(x_bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+    y = torch.empty_like(x)
+    mask = torch.empty(n, dtype=torch.uint8, device=DEV)
+    z = torch.empty(n, dtype=torch.float32, device=DEV)
+    yo, mo = oracle.dropout(args, oracle.BF16, 0.1, 5, 0, x_bits)
+    zo = oracle.normal_f64_values(args, 0.0, 1.0, 5, 4096).reshape(-1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        v.vesrng_dropout(sh, v.BF16, 0.1, 5, 0, x, y, mask)      # warm-up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            v.vesrng_dropout(sh, v.BF16, 0.1, 5, 0, x, y, mask)
+            v.vesrng_normal(sh, v.F32, 0.0, 1.0, 5, 4096, z)
+    for replay in range(3):
+        y.fill_(1.0)
+        mask.fill_(9)
+        z.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().reshape(lshape), mo), replay
+        assert np.array_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(lshape), yo), replay
+        err = np.abs(z.cpu().numpy().astype(np.float64) - zo)
+        assert (err <= 1e-6 * np.maximum(np.abs(zo), 1.0)).all(), replay
