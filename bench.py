@@ -103,6 +103,33 @@ def time_batch(torch, launch, reps, warmup):
     return a.elapsed_time(b) / reps
 
 
+def time_graph(torch, launch, reps):
+    """Per-launch time of `reps` back-to-back launches replayed from a captured HIP graph: the
+    GPU-side cost without the host's issue rate (the library only enqueues kernels, so its calls
+    can be captured)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        launch(0)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for k in range(reps):
+                launch(k)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) / reps)
+    return sorted(times)[len(times) // 2]
+
+
 def measured_ceilings(v, torch):
     """Rates of the plain probe kernels on this machine, in this run: what bare 128-bit stores,
     a 16-byte copy, the dropout kernel's access pattern without arithmetic, and the generator
@@ -249,7 +276,10 @@ def main():
         for wl, copies in ((W.C1, 256), (W.C2, 16), (W.C3, 32), (W.C4, 8), (W.C5_INTERLEAVED, 1)):
             launch, numel, nb = make_launcher(v, W, torch, wl, wl.bench_coord, copies)
             avg = time_batch(torch, launch, max(50, a.steps), 5)
+            per_launch_graph = time_graph(torch, launch, 4 * copies if copies > 1 else 8)
             extra[wl.name.split()[0] + ("i" if wl is W.C5_INTERLEAVED else "")] = {
+                "graph_replay_us_per_launch": per_launch_graph * 1e3,
+                "graph_replay_gb_per_s": nb / (per_launch_graph * 1e-3) / 1e9,
                 "workload": wl.name, "elements": numel, "algorithmic_bytes": nb, "avg_launch_us": avg * 1e3,
                 "gb_per_s": nb / (avg * 1e-3) / 1e9, "gsamples_per_s": numel / (avg * 1e-3) / 1e9,
                 "pct_hbm_peak": 100 * nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_cycled": copies,
