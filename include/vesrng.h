@@ -22,7 +22,9 @@
  *     row-major buffers holding exactly the rank's local shard (local_numel
  *     elements), base address aligned to 16 bytes.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
- *     Kernels are enqueued and the call returns without synchronising.
+ *     Kernels are enqueued and the call returns without synchronising.  The
+ *     device that owns the buffers and the stream must be the calling thread's
+ *     current HIP device.  The calls can be captured into a HIP graph.
  *   - The library allocates no device memory, keeps no RNG state (the state is
  *     the caller's (seed, offset)) and is re-entrant.
  *   - Errors: a vesrng_status is returned; on any error nothing is launched and
