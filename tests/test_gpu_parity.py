@@ -666,3 +666,32 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         assert np.array_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(lshape), yo), replay
         err = np.abs(z.cpu().numpy().astype(np.float64) - zo)
         assert (err <= 1e-6 * np.maximum(np.abs(zo), 1.0)).all(), replay
+
+
+@pytest.mark.parametrize("label,shape", [("262 KB", [8, 16, 8, 8, 8]), ("64 MB", [16, 32, 32, 32, 32]),
+                                          ("1 GB", [32, 64, 32, 64, 64])])
+def test_table5_sizes_5d_double_sharding(label, shape):
+    """The paper's per-operator table at its own tensor sizes (fp32 element counts of 262 KB, 64 MB
+    and 1 GB; the 16 GB point is test_wide_index_path...): 5-D tensors, sharded on two different
+    dimensions and twice on the same dimension, one rank of each checked against the threaded oracle."""
+    numel = int(np.prod(shape))
+    assert numel * 4 in (262144, 64 << 20, 1 << 30)
+    seed, offset = 20240611, 1 << 20
+    for mesh, pls, coord in (([2, 2], [("S", 1), ("S", 3)], [1, 0]), ([2, 4], [("S", 4), ("S", 4)], [1, 2]),
+                             ([4], [("S", 0)], [3])):
+        args = (shape, mesh, pls, coord)
+        what = "%s %s" % (label, args)
+        say(what)
+        got = gpu_fill("uniform", "f32", args, seed, offset)
+        want = oracle.uniform(args, oracle.F32, 0.0, 1.0, seed, offset, threads=THREADS)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), what
+        del got, want
+        got = gpu_fill("normal", "bf16", args, seed, offset, mean=0.0, std=0.02)
+        check_normal(got, args, "bf16", 0.0, 0.02, seed, offset, what)
+        del got
+        n = oracle.local_shape(*args)[1]
+        x = W.bf16_bits_from_f32(np.random.default_rng(n % 1000).standard_normal(n, dtype=np.float32))
+        y, m = gpu_dropout("bf16", args, 0.1, seed, offset, x)
+        yo, mo = oracle.dropout(args, oracle.BF16, 0.1, seed, offset, x, threads=THREADS)
+        assert np.array_equal(m, mo), what
+        assert_float_bits_equal(y, yo, what)
