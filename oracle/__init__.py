@@ -23,7 +23,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 _KIND = {"R": 0, "S": 1, "IS": 2}
 _lib = None
 
@@ -60,6 +60,12 @@ def lib():
         L.oracle_bf16_from_float.argtypes = [C.c_float]
         L.oracle_float_from_bf16.restype = C.c_float
         L.oracle_float_from_bf16.argtypes = [C.c_uint16]
+        L.oracle_uniform_f16.restype = C.c_uint16
+        L.oracle_uniform_f16.argtypes = [C.c_uint32, C.c_float, C.c_float]
+        L.oracle_f16_from_double.restype = C.c_uint16
+        L.oracle_f16_from_double.argtypes = [C.c_double]
+        L.oracle_double_from_f16.restype = C.c_double
+        L.oracle_double_from_f16.argtypes = [C.c_uint16]
         L.oracle_advance_offset.restype = C.c_uint64
         L.oracle_advance_offset.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_uint64,
                                             C.c_uint64]
@@ -148,6 +154,18 @@ def bf16_from_float(v):
 
 def float_from_bf16(h):
     return lib().oracle_float_from_bf16(h)
+
+
+def uniform_f16(x, low=0.0, high=1.0):
+    return lib().oracle_uniform_f16(x, low, high)
+
+
+def f16_from_double(v):
+    return lib().oracle_f16_from_double(v)
+
+
+def double_from_f16(h):
+    return lib().oracle_double_from_f16(h)
 
 
 def local_shape(global_shape, mesh_shape, placements, mesh_coord):

@@ -117,6 +117,9 @@ float oracle_dropout_scale(double p) { return dropout_scale(p); }
 uint16_t oracle_bf16_from_double(double v) { return bf16_from_double(v); }
 uint16_t oracle_bf16_from_float(float v) { return bf16_from_float(v); }
 float oracle_float_from_bf16(uint16_t h) { return float_from_bf16(h); }
+uint16_t oracle_uniform_f16(uint32_t x, float low, float high) { return uniform_16(kF16, x, low, high); }
+uint16_t oracle_f16_from_double(double v) { return f16_from_double(v); }
+double oracle_double_from_f16(uint16_t h) { return double_from_f16(h); }
 
 // local_shape[ndim] and *local_numel of the rank's shard.
 int oracle_local_shape(const FlatSharding* f, int64_t* local_shape, int64_t* local_numel, char* err,

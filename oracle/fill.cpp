@@ -64,6 +64,44 @@ uint16_t bf16_from_double(double v) {
 
 uint16_t bf16_from_float(float v) { return bf16_from_double(static_cast<double>(v)); }
 
+// binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits.
+double double_from_f16(uint16_t h) {
+  const int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  double mag;
+  if (e == 31) mag = m ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+  else if (e == 0) mag = std::ldexp(static_cast<double>(m), -24);             // subnormal: m * 2^-24
+  else mag = std::ldexp(1.0 + static_cast<double>(m) / 1024.0, e - 15);      // (1 + m / 2^10) * 2^(e - 15)
+  return sign ? -mag : mag;
+}
+
+// The non-negative patterns 0 .. 0x7C00 are ordered like their values, so the two
+// neighbours of |v| are found by search; infinity takes part in the comparison at
+// 2^16, where the next value of the format would sit.
+uint16_t f16_from_double(double v) {
+  if (std::isnan(v)) return 0x7E00;
+  const uint16_t sign = std::signbit(v) ? 0x8000 : 0;
+  const double mag = std::fabs(v);
+  auto val = [](int32_t pat) { return pat == 0x7C00 ? 65536.0 : double_from_f16(static_cast<uint16_t>(pat)); };
+  if (mag >= 65536.0) return static_cast<uint16_t>(sign | 0x7C00);
+  int32_t lo = 0, hi = 0x7C00;  // val(lo) <= mag < val(hi)
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) / 2;
+    if (val(mid) <= mag) lo = mid;
+    else hi = mid;
+  }
+  const double below = mag - val(lo), above = val(hi) - mag;
+  int32_t best;
+  if (below < above) best = lo;
+  else if (above < below) best = hi;
+  else best = (lo % 2 == 0) ? lo : hi;
+  return static_cast<uint16_t>(sign | static_cast<uint16_t>(best));
+}
+
+uint16_t round_16(DType dt, double v) { return dt == kF16 ? f16_from_double(v) : bf16_from_double(v); }
+float value_16(DType dt, uint16_t h) {
+  return dt == kF16 ? static_cast<float>(double_from_f16(h)) : float_from_bf16(h);  // exact either way
+}
+
 float uniform_f32(uint32_t x, float low, float high) {
   const float u = fraction24(x);
   const float width = high - low;  // rounded once
@@ -73,14 +111,15 @@ float uniform_f32(uint32_t x, float low, float high) {
   return r;
 }
 
-uint16_t uniform_bf16(uint32_t x, float low, float high) {
+uint16_t uniform_16(DType dt, uint32_t x, float low, float high) {
   const float r = uniform_f32(x, low, high);
-  uint16_t h = bf16_from_float(r);
-  if (high > low && float_from_bf16(h) >= high) {
-    // Largest bfloat16 strictly below high.
-    uint16_t top = bf16_from_float(high);
-    if (float_from_bf16(top) >= high) {
-      const float t = float_from_bf16(top);
+  uint16_t h = round_16(dt, static_cast<double>(r));
+  if (high > low && value_16(dt, h) >= high) {
+    // Largest value of the format strictly below high (sign-magnitude patterns: one
+    // step down is pattern - 1 above zero and pattern + 1 below it).
+    uint16_t top = round_16(dt, static_cast<double>(high));
+    if (value_16(dt, top) >= high) {
+      const float t = value_16(dt, top);
       if (t > 0.0f) top = static_cast<uint16_t>(top - 1);
       else if (t == 0.0f) top = 0x8001;  // just below zero
       else top = static_cast<uint16_t>(top + 1);
@@ -89,6 +128,8 @@ uint16_t uniform_bf16(uint32_t x, float low, float high) {
   }
   return h;
 }
+
+uint16_t uniform_bf16(uint32_t x, float low, float high) { return uniform_16(kBF16, x, low, high); }
 
 double normal_f64(uint32_t xa, uint32_t xb, bool odd, double mean, double std) {
   const double pi = 3.14159265358979323846264338327950288;
@@ -118,7 +159,7 @@ void uniform(const Sharding& s, DType dt, double low, double high, uint64_t seed
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
     const uint32_t x = draw_at(s, seed, offset, j);
     if (dt == kF32) static_cast<float*>(out)[i] = uniform_f32(x, lo, hi);
-    else static_cast<uint16_t*>(out)[i] = uniform_bf16(x, lo, hi);
+    else static_cast<uint16_t*>(out)[i] = uniform_16(dt, x, lo, hi);
   });
 }
 
@@ -139,7 +180,7 @@ void normal(const Sharding& s, DType dt, double mean, double std, uint64_t seed,
   for_each_local(s, i_begin, i_end, [&](int64_t i, uint64_t j) {
     const double v = normal_at(s, seed, offset, j, mean, std);
     if (dt == kF32) static_cast<float*>(out)[i] = static_cast<float>(v);
-    else static_cast<uint16_t*>(out)[i] = bf16_from_double(v);
+    else static_cast<uint16_t*>(out)[i] = round_16(dt, v);
   });
 }
 
@@ -162,9 +203,9 @@ void dropout(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t offs
       const float xin = static_cast<const float*>(x)[i];
       static_cast<float*>(y)[i] = keep ? xin * scale : 0.0f;
     } else {
-      const float xin = float_from_bf16(static_cast<const uint16_t*>(x)[i]);
+      const float xin = value_16(dt, static_cast<const uint16_t*>(x)[i]);
       const float prod = xin * scale;  // rounded to fp32 first
-      static_cast<uint16_t*>(y)[i] = keep ? bf16_from_float(prod) : uint16_t{0};
+      static_cast<uint16_t*>(y)[i] = keep ? round_16(dt, static_cast<double>(prod)) : uint16_t{0};
     }
   });
 }
@@ -182,10 +223,10 @@ void dropout_add(const Sharding& s, DType dt, double p, uint64_t seed, uint64_t 
       const float kept = keep ? prod : 0.0f;
       static_cast<float*>(y)[i] = static_cast<const float*>(residual)[i] + kept;
     } else {
-      const float prod = float_from_bf16(static_cast<const uint16_t*>(x)[i]) * scale;
+      const float prod = value_16(dt, static_cast<const uint16_t*>(x)[i]) * scale;
       const float kept = keep ? prod : 0.0f;
-      const float sum = float_from_bf16(static_cast<const uint16_t*>(residual)[i]) + kept;
-      static_cast<uint16_t*>(y)[i] = bf16_from_float(sum);
+      const float sum = value_16(dt, static_cast<const uint16_t*>(residual)[i]) + kept;
+      static_cast<uint16_t*>(y)[i] = round_16(dt, static_cast<double>(sum));
     }
   });
 }

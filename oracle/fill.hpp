@@ -11,7 +11,7 @@
 
 namespace oracle {
 
-enum DType : int32_t { kF32 = 0, kBF16 = 1 };
+enum DType : int32_t { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
 // --- value of ONE global element -------------------------------------------
 
@@ -21,6 +21,8 @@ enum DType : int32_t { kF32 = 0, kBF16 = 1 };
 float uniform_f32(uint32_t x, float low, float high);
 // Same value, then rounded to bfloat16 (nearest even) with the same pull-back.
 uint16_t uniform_bf16(uint32_t x, float low, float high);
+// The same for either 16-bit dtype (kBF16 or kF16, IEEE binary16).
+uint16_t uniform_16(DType dt, uint32_t x, float low, float high);
 
 // Box-Muller in double.  `xa` feeds the radius, `xb` the angle; `odd` picks
 // sine (odd stream position) or cosine (even).  Returns mean + std * n.
@@ -34,6 +36,13 @@ float dropout_scale(double p);
 uint16_t bf16_from_double(double v);
 uint16_t bf16_from_float(float v);
 float float_from_bf16(uint16_t h);
+// IEEE binary16: the value of a bit pattern, read off the format's definition, and
+// nearest-even rounding by search over the patterns.  round_16 / value_16 take either
+// 16-bit dtype.
+double double_from_f16(uint16_t h);
+uint16_t f16_from_double(double v);
+uint16_t round_16(DType dt, double v);
+float value_16(DType dt, uint16_t h);
 
 // --- a rank's local tensor, elements [i_begin, i_end) ------------------------
 void raw_u32(const Sharding& s, uint64_t seed, uint64_t offset, int64_t i_begin, int64_t i_end,

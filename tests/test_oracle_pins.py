@@ -485,3 +485,73 @@ def test_dropout_threshold_rounds_to_nearest():
     assert oracle.dropout_threshold(0.45) == 9227469
     assert oracle.dropout_threshold(0.55) == 7549747      # 7549747.2 rounds down
     assert oracle.dropout_threshold(2.0 ** -25) == 2 ** 24  # 2^24 - 0.5 rounds half up to 2^24: nothing is dropped
+
+
+# ---------------------------------------------------------- binary16 ----------
+def test_f16_conversions_match_numpy_on_every_pattern_and_midpoint():
+    """numpy's float16 is an independent implementation of IEEE binary16: every bit pattern decodes to
+    the same value, and rounding agrees on random doubles over 15 decades, on every midpoint between
+    neighbouring values (ties to even), just beside the midpoints, and at the overflow boundary."""
+    pats = np.arange(65536, dtype=np.uint16)
+    vals = pats.view(np.float16).astype(np.float64)
+    for h in range(65536):
+        v = oracle.double_from_f16(h)
+        assert v == vals[h] or (math.isnan(v) and math.isnan(vals[h])), hex(h)
+    rng = np.random.default_rng(1)
+    mids = (vals[:0x7BFF] + vals[1:0x7C00]) / 2
+    xs = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-9, 6, 20000), mids, -mids,
+                         mids * (1 + 2.0 ** -40), mids * (1 - 2.0 ** -40),
+                         [0.0, -0.0, 65504, 65519.99, 65520, 65535, 65536, 1e9, -1e9, 2.0 ** -24, 2.0 ** -25,
+                          2.0 ** -25 * 1.0000001, 2.0 ** -26, np.inf, -np.inf]])
+    with np.errstate(over="ignore"):
+        ref = xs.astype(np.float16).view(np.uint16)
+    for x, r in zip(xs, ref):
+        assert oracle.f16_from_double(float(x)) == int(r), repr(float(x))
+    assert oracle.f16_from_double(float("nan")) & 0x7C00 == 0x7C00 and oracle.f16_from_double(float("nan")) & 0x3FF
+    assert oracle.f16_from_double(1.0 + 2.0 ** -11) == 0x3C00        # tie -> even
+    assert oracle.f16_from_double(1.0 + 3 * 2.0 ** -11) == 0x3C02    # tie -> even
+    assert oracle.f16_from_double(65520.0) == 0x7C00 and oracle.f16_from_double(65519.999) == 0x7BFF
+
+
+def test_f16_operators_are_the_fp32_value_rounded_once():
+    """uniform: the fp32 value rounded to binary16 (numpy), pulled below `high` when the rounding reaches
+    it; normal: the double value rounded once; dropout and dropout + residual: fp32 product / sum rounded
+    once - all rebuilt here with numpy's float16."""
+    assert oracle.uniform_f16(0) == 0 and oracle.uniform_f16(0xFFFFFFFF) == 0x3BFF   # 1 - 2^-24 rounds to 1 -> pulled
+    assert oracle.uniform_f16(0x80000000) == 0x3800
+    rng = np.random.default_rng(3)
+    for low, high in ((0.0, 1.0), (-1.0, 1.0), (-0.03, 0.03), (2.0, 2.001), (-65504.0, 65504.0), (-3.0, 0.0)):
+        lo32, hi32 = np.float32(low), np.float32(high)
+        for x in list(rng.integers(0, 2 ** 32, 300)) + [0, 0xFFFFFFFF, 0xFFFFFF00, 0xFFFFFEFF]:
+            got = oracle.uniform_f16(int(x), low, high)
+            r32 = np.float32(oracle.uniform_f32(int(x), low, high))
+            h = np.float16(r32)
+            assert float(np.uint16(got).view(np.float16)) < float(hi32)
+            if float(h) < float(hi32):
+                assert got == int(h.view(np.uint16)), (low, high, hex(int(x)))
+            else:   # pulled back: the largest binary16 below high
+                below = np.nextafter(np.float16(hi32), np.float16(-np.inf)) if float(np.float16(hi32)) >= float(hi32) \
+                    else np.float16(hi32)
+                assert got == int(below.view(np.uint16)), (low, high, hex(int(x)))
+    sh = ([6, 10], [2], [("S", 1)], [1])
+    v = oracle.normal_f64_values(sh, 0.5, 3.0, 4, 8).reshape(-1)
+    assert np.array_equal(oracle.normal(sh, oracle.F16, 0.5, 3.0, 4, 8).reshape(-1), v.astype(np.float16).view(np.uint16))
+    with np.errstate(over="ignore"):
+        big = oracle.normal(sh, oracle.F16, 0.0, 40000.0, 4, 8).reshape(-1)
+        vb = oracle.normal_f64_values(sh, 0.0, 40000.0, 4, 8).reshape(-1)
+        assert np.array_equal(big, vb.astype(np.float16).view(np.uint16)) and (big & 0x7FFF == 0x7C00).any()
+    x = np.concatenate([rng.standard_normal(24) * 100, [0.0, -0.0, 6.0e-8, -6.0e-8, 65504.0, -65504.0]]
+                       ).astype(np.float16)
+    r = (rng.standard_normal(30) * 100).astype(np.float16)
+    scale = np.float32(oracle.dropout_scale(0.3))
+    y, m = oracle.dropout(sh, oracle.F16, 0.3, 4, 0, x.view(np.uint16))
+    keep = m.reshape(-1).astype(bool)
+    md = oracle.dropout(sh, oracle.F32, 0.3, 4, 0, x.astype(np.float32))[1]
+    assert np.array_equal(m, md) and keep.any() and not keep.all()
+    with np.errstate(over="ignore"):
+        prod = x.astype(np.float32) * scale
+        want = np.where(keep, prod.astype(np.float16).view(np.uint16), np.uint16(0))
+        assert np.array_equal(y.reshape(-1), want)
+        y2, m2 = oracle.dropout_add(sh, oracle.F16, 0.3, 4, 0, x.view(np.uint16), r.view(np.uint16))
+        total = r.astype(np.float32) + np.where(keep, prod, np.float32(0))
+        assert np.array_equal(m2, m) and np.array_equal(y2.reshape(-1), total.astype(np.float16).view(np.uint16))
