@@ -59,7 +59,9 @@ typedef enum {
   VESRNG_ERR_ALIGN = 12         /* a device pointer is not 16-byte aligned */
 } vesrng_status;
 
-typedef enum { VESRNG_F32 = 0, VESRNG_BF16 = 1 } vesrng_dtype;
+/* Element type of out / x / y: IEEE binary32, bfloat16, IEEE binary16.  Every operator computes
+ * in fp32 and rounds once (nearest even) to the 16-bit types. */
+typedef enum { VESRNG_F32 = 0, VESRNG_BF16 = 1, VESRNG_F16 = 2 } vesrng_dtype;
 
 /* Placement of the tensor on ONE mesh dimension (Section 2.2; Appendix A).
  * VESRNG_PARTIAL is listed so that callers can pass DTensor metadata through
@@ -131,7 +133,8 @@ VESRNG_API vesrng_status vesrng_raw_u32(const vesrng_sharding* s, uint64_t seed,
 
 /* Uniform in [low, high).  u = (draw >> 8) * 2^-24, value = fl(fl(u * fl(high - low)) + low)
  * in fp32; a value that reaches high becomes the largest representable value
- * below high.  BF16: the fp32 value rounded to nearest even, same upper guard.
+ * below high.  BF16 / F16: the fp32 value rounded to nearest even, same upper guard
+ * (F16: low and high must lie within +-65504, else VESRNG_ERR_BAD_PARAM).
  * Covers Table 5's uniform_, rand_like and kaiming_uniform_ (pass +-bound). */
 VESRNG_API vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, double low, double high,
                              uint64_t seed, uint64_t offset, void* out, void* hip_stream);
@@ -140,7 +143,7 @@ VESRNG_API vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype d
  * u1 = ((a >> 8) + 1) * 2^-24, u2 = (b >> 8) * 2^-24, r = sqrt(-2 ln u1); the
  * even stream position takes r cos(2 pi u2), the odd one r sin(2 pi u2).
  * Evaluated in fp32; agrees with the double-precision definition to
- * 1e-6 * max(|value|, std) (F32) or one bfloat16 ulp (BF16).
+ * 1e-6 * max(|value|, std) (F32) or one ulp of the 16-bit type (BF16, F16).
  * Covers Table 5's normal_ and randn_like. */
 VESRNG_API vesrng_status vesrng_normal(const vesrng_sharding* s, vesrng_dtype dtype, double mean, double std,
                             uint64_t seed, uint64_t offset, void* out, void* hip_stream);

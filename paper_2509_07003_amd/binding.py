@@ -10,7 +10,7 @@ import os
 
 from . import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 _KIND = {"R": 0, "S": 1, "IS": 2, "P": 3}
 
 

@@ -44,6 +44,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // 16 / 8 bytes that are only 4-byte aligned: whole blocks inside a ragged run.
 struct __attribute__((packed, aligned(4))) U32x4Unaligned {
@@ -54,7 +55,7 @@ struct __attribute__((packed, aligned(4))) U32x2Unaligned {
 };
 
 constexpr int kThreads = 256;
-constexpr int kF32 = 0, kBF16 = 1;
+constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
 
 template <typename IT>
 struct SignedOf;
@@ -68,12 +69,31 @@ struct SignedOf<uint64_t> {
 };
 
 // ---- conversions ---------------------------------------------------------------
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+// Two fp32 values rounded (nearest even) to a pair of 16-bit floats of dtype DT, low half first,
+// and the exact fp32 value of either half.
+template <int DT>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+  if constexpr (DT == kF16) {
+    // The values are fp32 results that get ONE more rounding.  Seen through, the compiler merges
+    // the producing multiply with this conversion into a mixed-precision fma whose +0 addend
+    // turns a product of -0 into +0; the empty asm keeps the two steps apart.
+    asm("" : "+v"(lo));
+    asm("" : "+v"(hi));
+  }
   const f32x2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32, RNE
+  if constexpr (DT == kBF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32
+  else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));                          // v_cvt_f16_f32 x2
 }
-__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+template <int DT>
+__device__ __forceinline__ float lo16(uint32_t pair) {
+  if constexpr (DT == kBF16) return __uint_as_float(pair << 16);
+  else return static_cast<float>(__builtin_bit_cast(f16x2, pair)[0]);
+}
+template <int DT>
+__device__ __forceinline__ float hi16(uint32_t pair) {
+  if constexpr (DT == kBF16) return __uint_as_float(pair & 0xFFFF0000u);
+  else return static_cast<float>(__builtin_bit_cast(f16x2, pair)[1]);
+}
 
 __device__ __forceinline__ float fraction24(uint32_t x) {
   return static_cast<float>(x >> 8) * 0x1p-24f;  // exact
@@ -87,11 +107,12 @@ __device__ __forceinline__ float uniform_value(uint32_t x, const OpParams& prm) 
   return r >= prm.high ? prm.top_f32 : r;
 }
 
-// Two fp32 uniforms rounded to a bfloat16 pair (upper guard applied after rounding).
-__device__ __forceinline__ uint32_t uniform_bf16_pack(float a, float b, const OpParams& prm) {
-  uint32_t pair = pack_bf16(a, b);
-  if (bf16_lo(pair) >= prm.high) pair = (pair & 0xFFFF0000u) | prm.top_bf16;
-  if (bf16_hi(pair) >= prm.high) pair = (pair & 0x0000FFFFu) | (prm.top_bf16 << 16);
+// Two fp32 uniforms rounded to a 16-bit pair (upper guard applied after rounding).
+template <int DT>
+__device__ __forceinline__ uint32_t uniform_pack16(float a, float b, const OpParams& prm) {
+  uint32_t pair = pack16<DT>(a, b);
+  if (lo16<DT>(pair) >= prm.high) pair = (pair & 0xFFFF0000u) | prm.top_16;
+  if (hi16<DT>(pair) >= prm.high) pair = (pair & 0x0000FFFFu) | (prm.top_16 << 16);
   return pair;
 }
 
@@ -150,7 +171,7 @@ constexpr bool kIsDropout = (OP == kOpDropout || OP == kOpDropoutAdd);
 // OP: OpKind.  DT: output dtype.  A unit is what one thread stores: V elements.
 template <int OP, int DT>
 struct UnitOf {
-  static constexpr int kBlocks = (OP != kOpRaw && OP != kOpRandint && DT == kBF16) ? 2 : 1;
+  static constexpr int kBlocks = (OP != kOpRaw && OP != kOpRandint && DT != kF32) ? 2 : 1;
   static constexpr int kElems = 4 * kBlocks;
 };
 
@@ -193,15 +214,15 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
         for (int h = 0; h < 2; ++h) {  // two packed pairs per block
           const uint32_t pair = xv[2 * b + h];
           const bool k0 = keep_of(v[4 * b + 2 * h], prm), k1 = keep_of(v[4 * b + 2 * h + 1], prm);
-          const float p0 = __fmul_rn(bf16_lo(pair), prm.scale);
-          const float p1 = __fmul_rn(bf16_hi(pair), prm.scale);
+          const float p0 = __fmul_rn(lo16<DT>(pair), prm.scale);
+          const float p1 = __fmul_rn(hi16<DT>(pair), prm.scale);
           // Select before rounding: a dropped element becomes +0 whatever x held.
           float y0 = k0 ? p0 : 0.0f, y1 = k1 ? p1 : 0.0f;
           if constexpr (kAdd) {
-            y0 = __fadd_rn(bf16_lo(rv[2 * b + h]), y0);
-            y1 = __fadd_rn(bf16_hi(rv[2 * b + h]), y1);
+            y0 = __fadd_rn(lo16<DT>(rv[2 * b + h]), y0);
+            y1 = __fadd_rn(hi16<DT>(rv[2 * b + h]), y1);
           }
-          y[2 * b + h] = pack_bf16(y0, y1);
+          y[2 * b + h] = pack16<DT>(y0, y1);
           m[b] |= ((k0 ? 1u : 0u) | (k1 ? 0x100u : 0u)) << (16 * h);
         }
       }
@@ -217,7 +238,7 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float a = __uint_as_float(v[2 * q]), b = __uint_as_float(v[2 * q + 1]);
-        o[q] = (OP == kOpUniform) ? uniform_bf16_pack(a, b, prm) : pack_bf16(a, b);
+        o[q] = (OP == kOpUniform) ? uniform_pack16<DT>(a, b, prm) : pack16<DT>(a, b);
       }
     }
     __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + u);
@@ -241,19 +262,19 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
       static_cast<float*>(out)[i] = kAdd ? __fadd_rn(static_cast<const float*>(prm.residual)[i], kept) : kept;
     } else {
       const uint32_t x = static_cast<const uint16_t*>(xin)[i];
-      float kept = keep ? __fmul_rn(__uint_as_float(x << 16), prm.scale) : 0.0f;
+      float kept = keep ? __fmul_rn(lo16<DT>(x), prm.scale) : 0.0f;
       if constexpr (kAdd) {
         const uint32_t r = static_cast<const uint16_t*>(prm.residual)[i];
-        kept = __fadd_rn(__uint_as_float(r << 16), kept);
+        kept = __fadd_rn(lo16<DT>(r), kept);
       }
-      static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pack_bf16(kept, 0.0f));
+      static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pack16<DT>(kept, 0.0f));
     }
     if (mask) mask[i] = keep ? 1 : 0;
   } else if constexpr (DT == kF32) {
     static_cast<uint32_t*>(out)[i] = v;
   } else {
     const float a = __uint_as_float(v);
-    const uint32_t pair = (OP == kOpUniform) ? uniform_bf16_pack(a, a, prm) : pack_bf16(a, a);
+    const uint32_t pair = (OP == kOpUniform) ? uniform_pack16<DT>(a, a, prm) : pack16<DT>(a, a);
     static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pair);
   }
 }
@@ -264,7 +285,7 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
 template <int OP>
 __device__ __forceinline__ void touch_params(const OpParams& prm) {
   if constexpr (OP == kOpUniform)
-    asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.high), "s"(prm.top_f32), "s"(prm.top_bf16),
+    asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.high), "s"(prm.top_f32), "s"(prm.top_16),
                  "s"(prm.unit_range));
   else if constexpr (OP == kOpNormal)
     asm volatile("" ::"s"(prm.mean), "s"(prm.stddev));
@@ -484,8 +505,8 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
       } else if ((li0 & 1) == 0) {
         const float a = __uint_as_float(v[0]), b = __uint_as_float(v[1]);
         const float c = __uint_as_float(v[2]), e = __uint_as_float(v[3]);
-        const uint32_t p01 = (OP == kOpUniform) ? uniform_bf16_pack(a, b, prm) : pack_bf16(a, b);
-        const uint32_t p23 = (OP == kOpUniform) ? uniform_bf16_pack(c, e, prm) : pack_bf16(c, e);
+        const uint32_t p01 = (OP == kOpUniform) ? uniform_pack16<DT>(a, b, prm) : pack16<DT>(a, b);
+        const uint32_t p23 = (OP == kOpUniform) ? uniform_pack16<DT>(c, e, prm) : pack16<DT>(c, e);
         *reinterpret_cast<U32x2Unaligned*>(static_cast<uint16_t*>(out) + li0) = U32x2Unaligned{p01, p23};
         return;
       }
@@ -645,29 +666,30 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   return launch_typed<OP, DT, uint64_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
 }
 
+// The floating-point operators, by output dtype.
+template <int OP>
+hipError_t launch_float(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
+                        uint8_t* mask, hipStream_t stream) {
+  switch (prm.dtype) {
+    case kF32: return launch_dt<OP, kF32>(g, offset, prm, x, out, mask, stream);
+    case kBF16: return launch_dt<OP, kBF16>(g, offset, prm, x, out, mask, stream);
+    case kF16: return launch_dt<OP, kF16>(g, offset, prm, x, out, mask, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 hipError_t launch_op(OpKind op, const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                      uint8_t* mask, hipStream_t stream) {
   if (g.local_numel == 0) return hipSuccess;
-  const bool bf16 = prm.dtype == kBF16;
   switch (op) {
-    case kOpRaw:
-      return launch_dt<kOpRaw, kF32>(g, offset, prm, x, out, mask, stream);
-    case kOpRandint:
-      return launch_dt<kOpRandint, kF32>(g, offset, prm, x, out, mask, stream);
-    case kOpUniform:
-      return bf16 ? launch_dt<kOpUniform, kBF16>(g, offset, prm, x, out, mask, stream)
-                  : launch_dt<kOpUniform, kF32>(g, offset, prm, x, out, mask, stream);
-    case kOpNormal:
-      return bf16 ? launch_dt<kOpNormal, kBF16>(g, offset, prm, x, out, mask, stream)
-                  : launch_dt<kOpNormal, kF32>(g, offset, prm, x, out, mask, stream);
-    case kOpDropout:
-      return bf16 ? launch_dt<kOpDropout, kBF16>(g, offset, prm, x, out, mask, stream)
-                  : launch_dt<kOpDropout, kF32>(g, offset, prm, x, out, mask, stream);
-    case kOpDropoutAdd:
-      return bf16 ? launch_dt<kOpDropoutAdd, kBF16>(g, offset, prm, x, out, mask, stream)
-                  : launch_dt<kOpDropoutAdd, kF32>(g, offset, prm, x, out, mask, stream);
+    case kOpRaw: return launch_dt<kOpRaw, kF32>(g, offset, prm, x, out, mask, stream);
+    case kOpRandint: return launch_dt<kOpRandint, kF32>(g, offset, prm, x, out, mask, stream);
+    case kOpUniform: return launch_float<kOpUniform>(g, offset, prm, x, out, mask, stream);
+    case kOpNormal: return launch_float<kOpNormal>(g, offset, prm, x, out, mask, stream);
+    case kOpDropout: return launch_float<kOpDropout>(g, offset, prm, x, out, mask, stream);
+    case kOpDropoutAdd: return launch_float<kOpDropoutAdd>(g, offset, prm, x, out, mask, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -17,7 +17,7 @@ struct OpParams {
   // uniform: value = u * width + low, guarded below `high`
   float width = 1.f, low = 0.f, high = 1.f;
   float top_f32 = 1.f;          // largest fp32 below high
-  uint32_t top_bf16 = 0;        // largest bfloat16 below high (bit pattern)
+  uint32_t top_16 = 0;          // largest value of a 16-bit dtype below high (bit pattern)
   uint32_t unit_range = 0;      // low == 0 and high == 1: the value is u itself
   // normal
   float mean = 0.f, stddev = 1.f;

@@ -35,17 +35,42 @@ uint32_t bf16_rne(float f) {
 }
 float bf16_value(uint32_t h) { return f32_from_bits(h << 16); }
 
-// Largest bfloat16 strictly below `high` (bit pattern), high finite.
-uint32_t bf16_below(float high) {
-  uint32_t h = bf16_rne(high) & 0xFFFFu;
-  if (bf16_value(h) >= high) {
-    const float t = bf16_value(h);
+// fp32 -> IEEE binary16, round to nearest even (finite inputs; 65520 and above become infinity).
+uint32_t f16_rne(float f) {
+  const uint32_t b = f32_bits(f), sign = (b >> 16) & 0x8000u, mag = b & 0x7FFFFFFFu;
+  if (mag >= 0x47800000u) return sign | 0x7C00u;  // 2^16 and above
+  if (mag < 0x38800000u)                          // below 2^-14: a multiple of 2^-24
+    return sign | static_cast<uint32_t>(std::nearbyint(std::ldexp(static_cast<double>(std::fabs(f)), 24)));
+  const uint32_t r = mag - (112u << 23);          // rebias the exponent from 127 to 15
+  return sign | ((r + 0xFFFu + ((r >> 13) & 1u)) >> 13);
+}
+float f16_value(uint32_t h) {
+  const int e = static_cast<int>((h >> 10) & 31u);
+  const float m = static_cast<float>(h & 1023u);
+  float mag;
+  if (e == 31) mag = std::numeric_limits<float>::infinity();
+  else if (e == 0) mag = std::ldexp(m, -24);
+  else mag = std::ldexp(1024.0f + m, e - 25);
+  return (h & 0x8000u) ? -mag : mag;
+}
+
+uint32_t round_16(vesrng_dtype dt, float f) { return (dt == VESRNG_F16 ? f16_rne(f) : bf16_rne(f)) & 0xFFFFu; }
+float value_16(vesrng_dtype dt, uint32_t h) { return dt == VESRNG_F16 ? f16_value(h) : bf16_value(h); }
+
+// Largest value of the 16-bit dtype strictly below `high` (bit pattern), high finite.  The
+// patterns are sign-magnitude: one step down is -1 above zero and +1 below it.
+uint32_t below_16(vesrng_dtype dt, float high) {
+  uint32_t h = round_16(dt, high);
+  if (value_16(dt, h) >= high) {
+    const float t = value_16(dt, h);
     if (t > 0.0f) h -= 1;
     else if (t == 0.0f) h = 0x8001u;
     else h += 1;
   }
   return h & 0xFFFFu;
 }
+
+bool known_float_dtype(vesrng_dtype dt) { return dt == VESRNG_F32 || dt == VESRNG_BF16 || dt == VESRNG_F16; }
 
 // Checks shared by every generating entry point; fills geometry and the seed.
 vesrng_status prepare(const vesrng_sharding* s, uint64_t seed, uint64_t offset, Geometry* g, OpParams* prm) {
@@ -70,7 +95,7 @@ vesrng_status dropout_common(OpKind op, const vesrng_sharding* s, vesrng_dtype d
   OpParams prm;
   const vesrng_status st = prepare(s, seed, offset, &g, &prm);
   if (st != VESRNG_OK) return st;
-  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  if (!known_float_dtype(dtype)) return VESRNG_ERR_DTYPE;
   if (!(p >= 0.0 && p <= 1.0)) return VESRNG_ERR_BAD_PARAM;
   if (g.local_numel == 0) return VESRNG_OK;
   if (!x || !y || (op == kOpDropoutAdd && !residual)) return VESRNG_ERR_NULL;
@@ -188,10 +213,12 @@ vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, doubl
   OpParams prm;
   const vesrng_status st = prepare(s, seed, offset, &g, &prm);
   if (st != VESRNG_OK) return st;
-  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  if (!known_float_dtype(dtype)) return VESRNG_ERR_DTYPE;
   const float lo = static_cast<float>(low), hi = static_cast<float>(high);
   if (!(low <= high) || !std::isfinite(lo) || !std::isfinite(hi) || !std::isfinite(hi - lo))
     return VESRNG_ERR_BAD_PARAM;
+  // binary16 has no finite value beyond +-65504: a wider range could not be honoured.
+  if (dtype == VESRNG_F16 && (lo < -65504.0f || hi > 65504.0f)) return VESRNG_ERR_BAD_PARAM;
   if (g.local_numel == 0) return VESRNG_OK;
   if (!out) return VESRNG_ERR_NULL;
   if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
@@ -202,10 +229,10 @@ vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, doubl
   prm.unit_range = (lo == 0.0f && hi == 1.0f) ? 1u : 0u;
   if (hi > lo) {
     prm.top_f32 = std::nextafterf(hi, lo);
-    prm.top_bf16 = bf16_below(hi);
+    prm.top_16 = dtype == VESRNG_F32 ? 0u : below_16(dtype, hi);
   } else {
     prm.top_f32 = hi;
-    prm.top_bf16 = bf16_rne(hi) & 0xFFFFu;
+    prm.top_16 = dtype == VESRNG_F32 ? 0u : round_16(dtype, hi);
   }
   return finish(launch_op(kOpUniform, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
 }
@@ -216,7 +243,7 @@ vesrng_status vesrng_normal(const vesrng_sharding* s, vesrng_dtype dtype, double
   OpParams prm;
   const vesrng_status st = prepare(s, seed, offset, &g, &prm);
   if (st != VESRNG_OK) return st;
-  if (dtype != VESRNG_F32 && dtype != VESRNG_BF16) return VESRNG_ERR_DTYPE;
+  if (!known_float_dtype(dtype)) return VESRNG_ERR_DTYPE;
   const float m = static_cast<float>(mean), sd = static_cast<float>(std);
   if (!(std >= 0.0) || !std::isfinite(m) || !std::isfinite(sd)) return VESRNG_ERR_BAD_PARAM;
   if (g.local_numel == 0) return VESRNG_OK;

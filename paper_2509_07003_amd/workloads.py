@@ -58,6 +58,16 @@ def bf16_bits_from_f32(a: np.ndarray) -> np.ndarray:
     return t.view(torch.int16).numpy().view(np.uint16)
 
 
+def f16_bits_from_f32(a: np.ndarray) -> np.ndarray:
+    """float32 -> IEEE binary16 bit patterns (nearest even; overflow becomes infinity)."""
+    with np.errstate(over="ignore"):
+        return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def bits16_from_f32(a: np.ndarray, dtype: str) -> np.ndarray:
+    return f16_bits_from_f32(a) if dtype == "f16" else bf16_bits_from_f32(a)
+
+
 def host_activations(shape, seed, kind="normal", dtype="bf16") -> np.ndarray:
     """Seeded synthetic dropout input on the host: N(0,1) values, or softmax-normalised rows of
     N(0,1) logits (attention probabilities).  Returns float32, or uint16 bf16 bit patterns."""
@@ -88,7 +98,8 @@ def adversarial_f32(n: int, seed: int) -> np.ndarray:
     rng = np.random.default_rng(seed)
     a = rng.standard_normal(n).astype(np.float32)
     specials = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-39, -1e-39, 1e-45, 3.3e38, -3.3e38,
-                         1.0, -1.0, 65504.0, 2.0 ** -126, 2.0 ** -133], dtype=np.float32)
+                         1.0, -1.0, 65504.0, 2.0 ** -126, 2.0 ** -133,
+                         6.0e-8, -6.0e-8, 3.0e-5, 6.1e-5, 60000.0, -65504.0], dtype=np.float32)  # binary16's edges
     idx = rng.permutation(n)[: min(n, 8 * len(specials))]
     a[idx] = np.resize(specials, idx.size)
     return a

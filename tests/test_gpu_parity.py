@@ -1,7 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
 seeded inputs, element by element.  Bars: raw draws, uniforms, dropout outputs and masks and
 integers are bit-exact; fp32 normals within 1e-6 * max(|ref|, std) of the double-precision
-definition; bf16 normals within one bfloat16 ulp (neighbouring value)."""
+definition; bf16 / fp16 normals within one ulp of the 16-bit type (neighbouring value)."""
 import itertools
 import os
 
@@ -23,6 +23,22 @@ def say(msg):
     print(msg, flush=True)
 
 
+# dtype name -> (torch dtype, library code, oracle code)
+DT = {"f32": (torch.float32, v.F32, oracle.F32), "bf16": (torch.bfloat16, v.BF16, oracle.BF16),
+      "f16": (torch.float16, v.F16, oracle.F16)}
+
+
+def to_device(a, dtype):
+    """numpy float32 array, or uint16 bit patterns of a 16-bit dtype -> device tensor of that dtype."""
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(a).reshape(-1).view(np.int16)).to(DEV).view(DT[dtype][0])
+
+
+def to_host(t, dtype):
+    return t.cpu().numpy() if dtype == "f32" else t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
 # ------------------------------------------------------------------ helpers ----
 def gpu_fill(op, dtype, sharding_args, seed, offset, **params):
     """Runs one fill through the C ABI; returns a numpy array of the local shard
@@ -38,14 +54,13 @@ def gpu_fill(op, dtype, sharding_args, seed, offset, **params):
         v.vesrng_randint(sh, params["low"], params["high"], seed, offset, out)
         res = out.cpu().numpy()
     else:
-        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-        out = torch.empty(max(n, 1), dtype=tdt, device=DEV)
-        code = v.F32 if dtype == "f32" else v.BF16
+        out = torch.empty(max(n, 1), dtype=DT[dtype][0], device=DEV)
+        code = DT[dtype][1]
         if op == "uniform":
             v.vesrng_uniform(sh, code, params.get("low", 0.0), params.get("high", 1.0), seed, offset, out)
         else:
             v.vesrng_normal(sh, code, params.get("mean", 0.0), params.get("std", 1.0), seed, offset, out)
-        res = out.cpu().numpy() if dtype == "f32" else out.view(torch.int16).cpu().numpy().view(np.uint16)
+        res = to_host(out, dtype)
     torch.cuda.synchronize()
     return res[:n].reshape(shape)
 
@@ -53,34 +68,33 @@ def gpu_fill(op, dtype, sharding_args, seed, offset, **params):
 def gpu_dropout(dtype, sharding_args, p, seed, offset, x_np, with_mask=True, in_place=False):
     sh = v.Sharding(*sharding_args)
     shape, n = v.vesrng_local_shape(sh)
-    if dtype == "f32":
-        x = torch.from_numpy(np.ascontiguousarray(x_np, dtype=np.float32).reshape(-1)).to(DEV)
-    else:
-        x = torch.from_numpy(np.ascontiguousarray(x_np).reshape(-1).view(np.int16)).to(DEV).view(torch.bfloat16)
+    x = to_device(x_np, dtype)
     y = x if in_place else torch.empty_like(x)
     mask = torch.full((max(n, 1),), 7, dtype=torch.uint8, device=DEV) if with_mask else None
-    v.vesrng_dropout(sh, v.F32 if dtype == "f32" else v.BF16, p, seed, offset, x, y, mask)
+    v.vesrng_dropout(sh, DT[dtype][1], p, seed, offset, x, y, mask)
     torch.cuda.synchronize()
-    yn = y.cpu().numpy() if dtype == "f32" else y.view(torch.int16).cpu().numpy().view(np.uint16)
+    yn = to_host(y, dtype)
     return yn[:n].reshape(shape), (mask.cpu().numpy()[:n].reshape(shape) if with_mask else None)
 
 
 def bf16_ordinal(bits):
-    """Monotone integer code of bfloat16 bit patterns (+0 and -0 coincide)."""
+    """Monotone integer code of the bit patterns of a 16-bit float, bfloat16 or binary16: both are
+    sign-magnitude (+0 and -0 coincide)."""
     b = bits.astype(np.int32)
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
 
 
-def assert_float_bits_equal(got, want, what):
-    """Bit-exact, except that any NaN matches any NaN (payloads are unspecified)."""
+def assert_float_bits_equal(got, want, what, dtype="bf16"):
+    """Bit-exact, except that any NaN matches any NaN (payloads are unspecified).  `dtype` names the
+    16-bit format when the arrays hold uint16 patterns."""
     if got.dtype == np.float32:
         g, w = got.view(np.uint32), want.view(np.uint32)
         nan_g, nan_w = np.isnan(got), np.isnan(want)
     else:
         g, w = got, want
-        nan_g = (got & 0x7F80) == 0x7F80
-        nan_g &= (got & 0x007F) != 0
-        nan_w = ((want & 0x7F80) == 0x7F80) & ((want & 0x007F) != 0)
+        expo, frac = (0x7C00, 0x03FF) if dtype == "f16" else (0x7F80, 0x007F)
+        nan_g = ((got & expo) == expo) & ((got & frac) != 0)
+        nan_w = ((want & expo) == expo) & ((want & frac) != 0)
     assert np.array_equal(nan_g, nan_w), what + ": NaN positions differ"
     bad = (g != w) & ~nan_g
     assert not bad.any(), "%s: %d mismatches, first at %s" % (what, bad.sum(), np.argwhere(bad)[:3].tolist())
@@ -98,23 +112,28 @@ def check_normal(got, sharding_args, dtype, mean, std, seed, offset, what, i_beg
         worst = float((err / tol).max()) if err.size else 0.0
         assert worst <= 1.0, "%s: error is %.3f of the tolerance" % (what, worst)
         return worst
-    # bfloat16: the kernel rounds an fp32 value that lies within the fp32 tolerance of the
+    # 16-bit outputs: the kernel rounds an fp32 value that lies within the fp32 tolerance of the
     # reference, so - rounding being monotone - its result must lie between the roundings of
-    # ref - tol and ref + tol.  Away from zero that is the reference value or its neighbour
-    # (one bfloat16 ulp); next to zero it also admits the other sign of a vanishing value.
+    # ref - tol and ref + tol.  Where the format's spacing exceeds 2 tol (|ref| > 2^(bits + 2) tol
+    # for `bits` fraction bits) that is the reference value or its neighbour: one ulp; closer to
+    # zero the interval spans a few of the ever finer steps, and the other sign of a vanishing value.
     tol = 1e-6 * np.maximum(np.abs(ref), std)
-    lo = bf16_ordinal(_bf16_bits(ref - tol))
-    hi = bf16_ordinal(_bf16_bits(ref + tol))
+    lo = bf16_ordinal(_bits16(ref - tol, dtype))
+    hi = bf16_ordinal(_bits16(ref + tol, dtype))
     go = bf16_ordinal(g)
     bad = (go < lo) | (go > hi)
     assert not bad.any(), "%s: %d values outside the rounding interval, first %s" % (what, bad.sum(), np.argwhere(bad)[:3].tolist())
-    assert (hi - lo)[np.abs(ref) > 1e-3 * std].max(initial=0) <= 1
-    want = oracle.normal(tuple(sharding_args), oracle.BF16, mean, std, seed, offset, i_begin=i_begin,
+    assert (hi - lo)[np.abs(ref) > (2.0 ** 12 if dtype == "f16" else 2.0 ** 9) * tol].max(initial=0) <= 1
+    want = oracle.normal(tuple(sharding_args), DT[dtype][2], mean, std, seed, offset, i_begin=i_begin,
                          i_end=i_end, threads=THREADS).reshape(-1)[sl]
     return float((g != want).mean()) if g.size else 0.0
 
 
-def _bf16_bits(a64):
+def _bits16(a64, dtype):
+    """float64 -> the 16-bit dtype, one rounding, by a library (torch for bfloat16, numpy for binary16)."""
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            return np.ascontiguousarray(a64).astype(np.float16).view(np.uint16)
     t = torch.from_numpy(np.ascontiguousarray(a64)).to(torch.bfloat16)
     return t.view(torch.int16).numpy().view(np.uint16)
 
@@ -695,3 +714,73 @@ def test_table5_sizes_5d_double_sharding(label, shape):
         yo, mo = oracle.dropout(args, oracle.BF16, 0.1, seed, offset, x, threads=THREADS)
         assert np.array_equal(m, mo), what
         assert_float_bits_equal(y, yo, what)
+
+
+# ------------------------------------------------------------- binary16 -------
+F16_CASES = [([64, 4096], [4], [("S", 0)], [3]),                                 # aligned
+             ([300, 333], [3], [("S", 1)], [1]),                                 # ragged column shard (tiled for dropout)
+             ([40, 7], [2], [("S", 1)], [1]),                                    # runs of 3: element-wise edges only
+             ([5, 6, 7, 8, 9], [2, 2], [("S", 1), ("S", 3)], [1, 0]),            # 5-D, two sharded dims
+             ([96], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1]),                   # not a box
+             ([33, 50], [2], [("S", 1)], [0], None, 64)]                         # virtual-thread layout
+
+
+def test_f16_fills_all_kernel_flavours():
+    """IEEE binary16 outputs: uniforms bit-exact (several ranges, the upper guard included), normals
+    within the rounding interval of the double-precision value."""
+    seed, offset = 99, 4096
+    for args in F16_CASES:
+        say("f16 fills %s" % (args,))
+        for low, high in ((0.0, 1.0), (-0.05, 0.05), (2.0, 2.001), (-65504.0, 65504.0)):
+            got = gpu_fill("uniform", "f16", args, seed, offset, low=low, high=high)
+            want = oracle.uniform(args, oracle.F16, low, high, seed, offset)
+            assert np.array_equal(got, want), (args, low, high)
+        for mean, std in ((0.0, 1.0), (0.0, 0.02), (3.0, 1e-4)):
+            got = gpu_fill("normal", "f16", args, seed, offset, mean=mean, std=std)
+            check_normal(got, args, "f16", mean, std, seed, offset, "normal f16 %s" % (args,))
+    # The guard at work on a long stream: every value stays below high although rounding reaches it.
+    n = 1 << 18
+    flat = ([n], [1], [("R",)], [0])
+    got = gpu_fill("uniform", "f16", flat, 77, 0)
+    assert np.array_equal(got, oracle.uniform(flat, oracle.F16, 0.0, 1.0, 77, 0, threads=THREADS))
+    assert got.max() == 0x3BFF and (got == 0x3BFF).sum() > n // 4096
+    sh = v.Sharding(*flat)
+    out = torch.empty(n, dtype=torch.float16, device=DEV)
+    for low, high in ((-70000.0, 1.0), (0.0, 65536.0)):
+        with pytest.raises(v.VesrngError) as e:
+            v.vesrng_uniform(sh, v.F16, low, high, 1, 0, out)
+        assert e.value.status == 7
+    with pytest.raises(v.VesrngError) as e:
+        v.vesrng_uniform(sh, 3, 0.0, 1.0, 1, 0, out)
+    assert e.value.status == 8
+
+
+def test_f16_dropout_and_residual_add_all_kernel_flavours():
+    seed, offset = 2025, 64
+    for k, args in enumerate(F16_CASES):
+        say("f16 dropout %s" % (args,))
+        sh = v.Sharding(*args)
+        lshape, n = v.vesrng_local_shape(sh)
+        with np.errstate(over="ignore"):
+            x = W.f16_bits_from_f32(W.adversarial_f32(n, seed=10 + k) * np.float32(3.0))
+        r = W.f16_bits_from_f32(W.adversarial_f32(n, seed=20 + k))
+        for p in (0.1, 0.0, 1.0, 0.5):
+            yo, mo = oracle.dropout(args, oracle.F16, p, seed, offset, x)
+            y, m = gpu_dropout("f16", args, p, seed, offset, x)
+            assert np.array_equal(m, mo), (args, p)
+            assert_float_bits_equal(y, yo, "dropout f16 %s p=%g" % (args, p), dtype="f16")
+            y2, _ = gpu_dropout("f16", args, p, seed, offset, x, with_mask=False, in_place=True)
+            assert_float_bits_equal(y2, yo, "dropout f16 in place %s p=%g" % (args, p), dtype="f16")
+        yo, mo = oracle.dropout_add(args, oracle.F16, 0.1, seed, offset, x, r)
+        xd, rd = to_device(x, "f16"), to_device(r, "f16")
+        yd = torch.empty_like(xd)
+        m = torch.empty(max(n, 1), dtype=torch.uint8, device=DEV)
+        v.vesrng_dropout_add(sh, v.F16, 0.1, seed, offset, xd, rd, yd, m)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy()[:n].reshape(lshape), mo), args
+        assert_float_bits_equal(to_host(yd, "f16")[:n].reshape(lshape), yo, "dropout_add f16 %s" % (args,), dtype="f16")
+    # Overflow on the way out is IEEE's: 60000 * 1.25 rounds to infinity on both sides.
+    flat = ([64], [1], [("R",)], [0])
+    x = W.f16_bits_from_f32(np.full(64, 60000.0, dtype=np.float32))
+    y, m = gpu_dropout("f16", flat, 0.2, 1, 0, x)
+    assert set(np.unique(y).tolist()) == {0, 0x7C00} and np.array_equal(y, oracle.dropout(flat, oracle.F16, 0.2, 1, 0, x)[0])

@@ -178,7 +178,7 @@ def test_error_paths_return_their_status_without_touching_the_gpu():
     assert _status(v.vesrng_uniform, ok, v.F32, 0.0, 1.0, 1, (1 << 64) - 16, buf) == 10
     assert _status(v.vesrng_normal, ok, v.F32, 0.0, -1.0, 1, 0, buf) == 7
     assert _status(v.vesrng_normal, ok, v.BF16, float("nan"), 1.0, 1, 0, buf) == 7
-    assert _status(v.vesrng_normal, ok, 2, 0.0, 1.0, 1, 0, buf) == 8
+    assert _status(v.vesrng_normal, ok, 3, 0.0, 1.0, 1, 0, buf) == 8
     assert _status(v.vesrng_dropout, ok, v.BF16, 1.5, 1, 0, buf, buf, None) == 7
     assert _status(v.vesrng_dropout, ok, v.BF16, -0.1, 1, 0, buf, buf, None) == 7
     assert _status(v.vesrng_dropout, ok, v.BF16, 0.1, 1, 0, None, buf, None) == 1
