@@ -784,3 +784,46 @@ def test_f16_dropout_and_residual_add_all_kernel_flavours():
     x = W.f16_bits_from_f32(np.full(64, 60000.0, dtype=np.float32))
     y, m = gpu_dropout("f16", flat, 0.2, 1, 0, x)
     assert set(np.unique(y).tolist()) == {0, 0x7C00} and np.array_equal(y, oracle.dropout(flat, oracle.F16, 0.2, 1, 0, x)[0])
+
+
+def test_concurrent_host_threads_on_their_own_streams():
+    """The library keeps no state between calls: four host threads issue different operators on
+    their own streams at the same time (ctypes drops the GIL for the call) and every result is
+    the one a lone call gives."""
+    import threading
+    jobs = [("raw", None, ([333, 517], [3], [("S", 1)], [1]), {}),
+            ("uniform", "bf16", ([64, 4096], [4], [("S", 0)], [2]), {}),
+            ("normal", "f32", ([5, 6, 7, 8, 9], [2, 2], [("S", 1), ("S", 3)], [1, 1]), {"mean": 1.0, "std": 2.0}),
+            ("uniform", "f16", ([96, 40], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1]), {"low": -1.0, "high": 1.0})]
+    alone = [gpu_fill(op, dt, args, 31, 64, **kw) for op, dt, args, kw in jobs]
+    results, errors = [None] * len(jobs), []
+
+    def work(k):
+        try:
+            op, dt, args, kw = jobs[k]
+            sh = v.Sharding(*args)
+            n = v.vesrng_local_shape(sh)[1]
+            stream = torch.cuda.Stream()
+            tdt = torch.int32 if op == "raw" else DT[dt][0]
+            outs = [torch.empty(n, dtype=tdt, device=DEV) for _ in range(50)]
+            for out in outs:
+                if op == "raw":
+                    v.vesrng_raw_u32(sh, 31, 64, out, stream=stream)
+                elif op == "uniform":
+                    v.vesrng_uniform(sh, DT[dt][1], kw.get("low", 0.0), kw.get("high", 1.0), 31, 64, out, stream=stream)
+                else:
+                    v.vesrng_normal(sh, DT[dt][1], kw["mean"], kw["std"], 31, 64, out, stream=stream)
+            stream.synchronize()
+            results[k] = [o.view(torch.int16 if o.element_size() == 2 else torch.int32).cpu().numpy() for o in outs]
+        except Exception as e:  # noqa: BLE001 - reported below, in the main thread
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for k, want in enumerate(alone):
+        for got in results[k]:
+            assert got.tobytes() == want.tobytes(), jobs[k]
