@@ -99,21 +99,19 @@ __device__ __forceinline__ float fraction24(uint32_t x) {
   return static_cast<float>(x >> 8) * 0x1p-24f;  // exact
 }
 
-__device__ __forceinline__ float uniform_value(uint32_t x, const OpParams& prm) {
-  // [0, 1): u * 1 + 0 is u itself and never reaches 1 (wave-uniform branch).
-  if (prm.unit_range) return fraction24(x);
-  const float scaled = __fmul_rn(fraction24(x), prm.width);
-  const float r = __fadd_rn(scaled, prm.low);
-  return r >= prm.high ? prm.top_f32 : r;
+// Uniform in [low, high): u * width + low as two fp32 operations, held at `cap`, the largest value
+// of the OUTPUT dtype below high.  Rounding to a 16-bit dtype is monotone, so capping the fp32
+// value first gives what "round, then pull a result that reached high back below it" gives.
+__device__ __forceinline__ float uniform_general(uint32_t x, const OpParams& prm) {
+  const float r = __fadd_rn(__fmul_rn(fraction24(x), prm.width), prm.low);
+  return __builtin_fminf(r, prm.cap);
 }
-
-// Two fp32 uniforms rounded to a 16-bit pair (upper guard applied after rounding).
+// [0, 1): the value is u itself; only a 16-bit dtype can round it up to 1.
 template <int DT>
-__device__ __forceinline__ uint32_t uniform_pack16(float a, float b, const OpParams& prm) {
-  uint32_t pair = pack16<DT>(a, b);
-  if (lo16<DT>(pair) >= prm.high) pair = (pair & 0xFFFF0000u) | prm.top_16;
-  if (hi16<DT>(pair) >= prm.high) pair = (pair & 0x0000FFFFu) | (prm.top_16 << 16);
-  return pair;
+__device__ __forceinline__ float uniform_unit(uint32_t x, const OpParams& prm) {
+  const float u = fraction24(x);
+  if constexpr (DT == kF32) return u;
+  else return __builtin_fminf(u, prm.cap);
 }
 
 // Box-Muller on one draw pair; hardware log2 / sqrt / sin / cos (sin and cos take
@@ -148,11 +146,17 @@ __device__ __forceinline__ int64_t randint_value(uint32_t x, const OpParams& prm
 // The per-element value of a whole generator block, as 32-bit patterns: fp32 bits for
 // uniform and normal (whatever the output dtype), the raw draws for the operators whose
 // conversion needs more than the draw (dropout needs x, randint widens to 64 bits).
-template <int OP>
+template <int OP, int DT>
 __device__ __forceinline__ void convert_block(const uint32_t (&d)[4], const OpParams& prm, uint32_t (&v)[4]) {
   if constexpr (OP == kOpUniform) {
+    if (prm.unit_range) {  // wave-uniform; the empty asm keeps it a branch instead of four selects
+      asm volatile("");
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(uniform_value(d[e], prm));
+      for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(uniform_unit<DT>(d[e], prm));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(uniform_general(d[e], prm));
+    }
   } else if constexpr (OP == kOpNormal) {
     float n[4];
     normal_pair(d[0], d[1], prm, n[0], n[1]);
@@ -175,6 +179,16 @@ struct UnitOf {
   static constexpr int kElems = 4 * kBlocks;
 };
 
+// Two consecutive integers as one 16-byte store into chunk `c` (elements 2c, 2c + 1) of out.
+__device__ __forceinline__ void store_randint_pair(uint32_t x0, uint32_t x1, const OpParams& prm, void* out,
+                                                   uint64_t c) {
+  const uint64_t r0 = static_cast<uint64_t>(randint_value(x0, prm));
+  const uint64_t r1 = static_cast<uint64_t>(randint_value(x1, prm));
+  const u32x4 o = {static_cast<uint32_t>(r0), static_cast<uint32_t>(r0 >> 32), static_cast<uint32_t>(r1),
+                   static_cast<uint32_t>(r1 >> 32)};
+  __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + c);
+}
+
 // Writes unit number `u` of the local tensor (elements [u*V, (u+1)*V)) from the V values
 // made by convert_block; dropout also consumes the 16 bytes of x loaded for the unit.
 template <int OP, int DT>
@@ -182,15 +196,8 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
                                           u32x4 xv, u32x4 rv, uint64_t u, void* out, uint8_t* mask) {
   constexpr int NB = UnitOf<OP, DT>::kBlocks;
   if constexpr (OP == kOpRandint) {
-    int64_t r[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = randint_value(v[e], prm);
-    const u32x4 lo = {static_cast<uint32_t>(r[0]), static_cast<uint32_t>(static_cast<uint64_t>(r[0]) >> 32),
-                      static_cast<uint32_t>(r[1]), static_cast<uint32_t>(static_cast<uint64_t>(r[1]) >> 32)};
-    const u32x4 hi = {static_cast<uint32_t>(r[2]), static_cast<uint32_t>(static_cast<uint64_t>(r[2]) >> 32),
-                      static_cast<uint32_t>(r[3]), static_cast<uint32_t>(static_cast<uint64_t>(r[3]) >> 32)};
-    __builtin_nontemporal_store(lo, static_cast<u32x4*>(out) + 2 * u);
-    __builtin_nontemporal_store(hi, static_cast<u32x4*>(out) + 2 * u + 1);
+    store_randint_pair(v[0], v[1], prm, out, 2 * u);
+    store_randint_pair(v[2], v[3], prm, out, 2 * u + 1);
   } else if constexpr (kIsDropout<OP>) {
     constexpr bool kAdd = (OP == kOpDropoutAdd);
     u32x4 y;
@@ -238,7 +245,7 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float a = __uint_as_float(v[2 * q]), b = __uint_as_float(v[2 * q + 1]);
-        o[q] = (OP == kOpUniform) ? uniform_pack16<DT>(a, b, prm) : pack16<DT>(a, b);
+        o[q] = pack16<DT>(a, b);
       }
     }
     __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + u);
@@ -274,7 +281,7 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
     static_cast<uint32_t*>(out)[i] = v;
   } else {
     const float a = __uint_as_float(v);
-    const uint32_t pair = (OP == kOpUniform) ? uniform_pack16<DT>(a, a, prm) : pack16<DT>(a, a);
+    const uint32_t pair = pack16<DT>(a, a);
     static_cast<uint16_t*>(out)[i] = static_cast<uint16_t>(pair);
   }
 }
@@ -285,8 +292,7 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
 template <int OP>
 __device__ __forceinline__ void touch_params(const OpParams& prm) {
   if constexpr (OP == kOpUniform)
-    asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.high), "s"(prm.top_f32), "s"(prm.top_16),
-                 "s"(prm.unit_range));
+    asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.cap), "s"(prm.unit_range));
   else if constexpr (OP == kOpNormal)
     asm volatile("" ::"s"(prm.mean), "s"(prm.stddev));
   else if constexpr (kIsDropout<OP>)
@@ -352,7 +358,14 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   // kernel arguments are fetched in one batch at the top.
   touch_params<OP>(prm);
   asm volatile("" ::"s"(out), "s"(mask));
-  const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  // randint writes 32 bytes per generator block.  Lane by lane that would be two stores of 16
+  // bytes at a 32-byte stride, which run at a third of the contiguous rate.  Instead the lane
+  // pair (2k, 2k+1) of a wave computes blocks k and 32 + k of the wave's 64 and the two trade
+  // halves, so that either store instruction writes 1 KiB without gaps.
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint64_t wave_base = t64 - lane;
+  if constexpr (OP == kOpRandint) t64 = wave_base + (lane >> 1) + ((lane & 1u) << 5);
   const bool live = t64 < plan.total_units;
   const uint64_t w64 = live ? t64 : 0;
   const IT w = static_cast<IT>(w64);
@@ -377,13 +390,29 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   for (int b = 0; b < NB; ++b) asm volatile("" : "+v"(d[b][0]), "+v"(d[b][1]), "+v"(d[b][2]), "+v"(d[b][3]));
   if constexpr (kIsDropout<OP>) asm volatile("" : "+v"(xv));
   if constexpr (OP == kOpDropoutAdd) asm volatile("" : "+v"(rv));
+  if constexpr (OP == kOpRandint) {
+    // All 64 lanes are still active here.  The even lane holds block k, the odd lane block
+    // 32 + k; each hands the half its partner stores to the neighbouring lane (quad_perm
+    // [1,0,3,2]).  Store A covers blocks 0..31 of the wave, store B blocks 32..63.
+    const bool odd = (lane & 1u) != 0u;
+    const uint32_t give0 = odd ? d[0][0] : d[0][2], give1 = odd ? d[0][1] : d[0][3];
+    const uint32_t got0 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(give0), 0xB1, 0xF, 0xF, false));
+    const uint32_t got1 = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(give1), 0xB1, 0xF, 0xF, false));
+    const uint64_t block_a = wave_base + (lane >> 1);  // the block whose half this lane writes in store A
+    const uint64_t chunk = 2 * wave_base + lane;
+    if (block_a < plan.total_units)
+      store_randint_pair(odd ? got0 : d[0][0], odd ? got1 : d[0][1], prm, out, chunk);
+    if (block_a + 32 < plan.total_units)
+      store_randint_pair(odd ? d[0][2] : got0, odd ? d[0][3] : got1, prm, out, chunk + 64);
+    return;
+  }
   if (!live) return;
 
   uint32_t v[V];
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     uint32_t vb[4];
-    convert_block<OP>(d[b], prm, vb);
+    convert_block<OP, DT>(d[b], prm, vb);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[4 * b + e] = vb[e];
   }
@@ -436,7 +465,7 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
     locate<NOUT>(plan, static_cast<IT>(wa + k), run, bi, run_pos);
     uint32_t d[4], v[4];
     philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
-    convert_block<OP>(d, prm, v);
+    convert_block<OP, DT>(d, prm, v);
     // The run occupies tile positions [run_lo, run_lo + run_len); lane e of this block sits at
     // rel + e.  A lane is written when it is inside both the run and the tile; the other lanes
     // of edge blocks (and the dead slots of runs that differ in phase) go to the dummy slot.
@@ -453,6 +482,19 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
   __syncthreads();
 
   // Stage B: one aligned unit per thread out of LDS.
+  if constexpr (OP == kOpRandint) {
+    // 16-byte chunks (two integers), consecutive threads on consecutive chunks: every store
+    // instruction of a wave writes 1 KiB without gaps.  local_numel is even here or the last
+    // element is written alone.
+    const uint32_t chunks = (static_cast<uint32_t>(lim) + 1u) >> 1;
+    for (uint32_t c = threadIdx.x; c < chunks; c += kThreads) {
+      if (2 * c + 1 < static_cast<uint32_t>(lim))
+        store_randint_pair(tile[2 * c], tile[2 * c + 1], prm, out, (i0 >> 1) + c);
+      else
+        static_cast<int64_t*>(out)[i0 + 2 * c] = randint_value(tile[2 * c], prm);
+    }
+    return;
+  }
   const uint64_t u = static_cast<uint64_t>(blockIdx.x) * ta.tile_units + threadIdx.x;
   const uint64_t e0 = u * V;
   if (threadIdx.x >= ta.tile_units || e0 >= i1) return;
@@ -494,7 +536,7 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
   if (!in_range || !s.any) return;
 
   uint32_t v[4];
-  convert_block<OP>(d, prm, v);
+  convert_block<OP, DT>(d, prm, v);
   const int64_t li0 = static_cast<int64_t>(s.li0);
   // Whole blocks of the fills leave as one store that is only element-aligned.
   if constexpr (OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) {
@@ -505,8 +547,7 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
       } else if ((li0 & 1) == 0) {
         const float a = __uint_as_float(v[0]), b = __uint_as_float(v[1]);
         const float c = __uint_as_float(v[2]), e = __uint_as_float(v[3]);
-        const uint32_t p01 = (OP == kOpUniform) ? uniform_pack16<DT>(a, b, prm) : pack16<DT>(a, b);
-        const uint32_t p23 = (OP == kOpUniform) ? uniform_pack16<DT>(c, e, prm) : pack16<DT>(c, e);
+        const uint32_t p01 = pack16<DT>(a, b), p23 = pack16<DT>(c, e);
         *reinterpret_cast<U32x2Unaligned*>(static_cast<uint16_t*>(out) + li0) = U32x2Unaligned{p01, p23};
         return;
       }
@@ -552,7 +593,7 @@ chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, co
                   static_cast<uint32_t>(tau >> 32), prm.key0, prm.key1, d);
     word = static_cast<uint32_t>(beta) & 3u;
   }
-  convert_block<OP>(d, prm, v);
+  convert_block<OP, DT>(d, prm, v);
   const uint32_t value = word == 0u ? v[0] : word == 1u ? v[1] : word == 2u ? v[2] : v[3];
   emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
 }

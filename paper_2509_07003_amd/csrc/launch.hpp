@@ -14,10 +14,9 @@ enum OpKind : int32_t { kOpRaw = 0, kOpUniform = 1, kOpNormal = 2, kOpDropout = 
 struct OpParams {
   uint32_t key0 = 0, key1 = 0;  // seed, low and high word
   int32_t dtype = 0;            // vesrng_dtype of out / x / y
-  // uniform: value = u * width + low, guarded below `high`
-  float width = 1.f, low = 0.f, high = 1.f;
-  float top_f32 = 1.f;          // largest fp32 below high
-  uint32_t top_16 = 0;          // largest value of a 16-bit dtype below high (bit pattern)
+  // uniform: value = min(u * width + low, cap)
+  float width = 1.f, low = 0.f;
+  float cap = 1.f;              // largest value of the output dtype below high (high itself if high == low)
   uint32_t unit_range = 0;      // low == 0 and high == 1: the value is u itself
   // normal
   float mean = 0.f, stddev = 1.f;

@@ -224,16 +224,10 @@ vesrng_status vesrng_uniform(const vesrng_sharding* s, vesrng_dtype dtype, doubl
   if (misaligned(out, 16)) return VESRNG_ERR_ALIGN;
   prm.dtype = dtype;
   prm.low = lo;
-  prm.high = hi;
   prm.width = hi - lo;
   prm.unit_range = (lo == 0.0f && hi == 1.0f) ? 1u : 0u;
-  if (hi > lo) {
-    prm.top_f32 = std::nextafterf(hi, lo);
-    prm.top_16 = dtype == VESRNG_F32 ? 0u : below_16(dtype, hi);
-  } else {
-    prm.top_f32 = hi;
-    prm.top_16 = dtype == VESRNG_F32 ? 0u : round_16(dtype, hi);
-  }
+  if (dtype == VESRNG_F32) prm.cap = hi > lo ? std::nextafterf(hi, lo) : hi;
+  else prm.cap = hi > lo ? value_16(dtype, below_16(dtype, hi)) : hi;
   return finish(launch_op(kOpUniform, g, offset, prm, nullptr, out, nullptr, static_cast<hipStream_t>(hip_stream)));
 }
 

@@ -334,15 +334,18 @@ def test_tiny_empty_and_zero_dim_tensors():
 def test_uniform_bounds_and_upper_guard():
     n = 1 << 16
     args = ([n], [1], [("R",)], [0])
-    for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16)):
-        for low, high in ((0.0, 1.0), (-1.0, 1.0), (0.0, 3.0), (5.0, 5.0), (-0.02, 0.02), (1e-3, 1.0 + 1e-3)):
+    for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16), ("f16", oracle.F16)):
+        for low, high in ((0.0, 1.0), (-1.0, 1.0), (0.0, 3.0), (5.0, 5.0), (-0.02, 0.02), (1e-3, 1.0 + 1e-3),
+                          (-3.0, 0.0), (2.0005, 2.001), (-1e-6, 1e-6), (0.1, 0.1), (-7.0, -6.99), (1.0, 1.0 + 2.0 ** -20)):
             got = gpu_fill("uniform", dtype, args, 77, 0, low=low, high=high)
             want = oracle.uniform(args, code, low, high, 77, 0)
-            assert_float_bits_equal(got, want, "uniform %s [%g,%g)" % (dtype, low, high))
-            vals = got if dtype == "f32" else torch.from_numpy(got.view(np.int16)).view(torch.bfloat16).float().numpy()
-            # bfloat16 cannot represent every low: the bound below is low rounded to the dtype.
-            floor = np.float32(low) if dtype == "f32" else np.float32(oracle.float_from_bf16(oracle.bf16_from_float(low)))
-            assert vals.min() >= floor and (vals.max() < np.float32(high) or low == high)
+            assert_float_bits_equal(got, want, "uniform %s [%g,%g)" % (dtype, low, high), dtype=dtype)
+            vals = got if dtype == "f32" else torch.from_numpy(got.view(np.int16)).view(DT[dtype][0]).float().numpy()
+            # A 16-bit dtype cannot represent every low: the bound below is low rounded to the dtype.
+            floor = np.float32(low) if dtype == "f32" else torch.tensor(low, dtype=torch.float32).to(DT[dtype][0]).float().numpy()
+            # ... nor every value below high when the range is narrower than its spacing.
+            narrow = dtype != "f32" and high - low < 0.01
+            assert vals.min() >= floor and (vals.max() < np.float32(high) or low == high or narrow)
 
 
 def test_dropout_degenerate_probabilities_special_values_in_place_and_no_mask():
