@@ -46,13 +46,11 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-// 16 / 8 bytes that are only 4-byte aligned: whole blocks inside a ragged run.
-struct __attribute__((packed, aligned(4))) U32x4Unaligned {
-  uint32_t a, b, c, d;
-};
-struct __attribute__((packed, aligned(4))) U32x2Unaligned {
-  uint32_t a, b;
-};
+// 16 / 8 bytes that are only 4-byte aligned: whole blocks inside a ragged run.  Vector types, so
+// that each leaves as ONE store (a struct of four words is four scalar stores to the optimiser,
+// which then shares the last one with the edge path and emits 12 + 4 bytes).
+typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
+typedef u32x2 u32x2_align4 __attribute__((aligned(4)));
 
 constexpr int kThreads = 256;
 constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
@@ -537,18 +535,22 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
 
   uint32_t v[4];
   convert_block<OP, DT>(d, prm, v);
+  // All four values exist before the stores are chosen: otherwise the compiler shares the
+  // last value's conversion between the whole-block and the edge path and splits the
+  // whole-block store into 12 + 4 bytes.
+  asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
   const int64_t li0 = static_cast<int64_t>(s.li0);
   // Whole blocks of the fills leave as one store that is only element-aligned.
   if constexpr (OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) {
     if (s.first == 0u && s.last == 4u) {
       if constexpr (OP == kOpRaw || DT == kF32) {
-        *reinterpret_cast<U32x4Unaligned*>(static_cast<uint32_t*>(out) + li0) = U32x4Unaligned{v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<u32x4_align4*>(static_cast<uint32_t*>(out) + li0) = u32x4{v[0], v[1], v[2], v[3]};
         return;
       } else if ((li0 & 1) == 0) {
         const float a = __uint_as_float(v[0]), b = __uint_as_float(v[1]);
         const float c = __uint_as_float(v[2]), e = __uint_as_float(v[3]);
         const uint32_t p01 = pack16<DT>(a, b), p23 = pack16<DT>(c, e);
-        *reinterpret_cast<U32x2Unaligned*>(static_cast<uint16_t*>(out) + li0) = U32x2Unaligned{p01, p23};
+        *reinterpret_cast<u32x2_align4*>(static_cast<uint16_t*>(out) + li0) = u32x2{p01, p23};
         return;
       }
     }
