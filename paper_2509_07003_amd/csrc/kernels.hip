@@ -12,9 +12,9 @@
 //  * ragged kernels: any run start / length (e.g. a column shard whose first
 //    column is 1366).  A thread owns one GLOBAL block and stores the lanes that
 //    fall inside the run; whole blocks leave as one element-aligned vector store.
-//    Used by the uniform and normal fills, and wherever runs are shorter than 16
-//    elements or the innermost global stride is not 1.
-//  * tiled kernels: ragged shards of the raw, randint and dropout operators.  A
+//    Used by the normal fills and the 16-bit uniform fills, and wherever runs are shorter
+//    than 16 elements or the innermost global stride is not 1.
+//  * tiled kernels: ragged shards of the raw, randint, fp32 uniform and dropout operators.  A
 //    workgroup owns a 128-byte aligned tile of the LOCAL tensor; its threads first
 //    own the GLOBAL blocks that intersect the tile and scatter their values into
 //    LDS at local positions, then each thread takes an aligned unit back out of
@@ -625,10 +625,12 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 enum Flavour { kAligned, kTiled, kRagged };
 // Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
 // through LDS doubles the rate of bf16 dropout (4.7 vs 2.4 TB/s) and helps the raw fill
-// (4.7 vs 4.1), but the uniform and normal fills spend too much arithmetic per element to
-// gain from it (4.0 vs 4.2 TB/s), so they keep the ragged kernel.
-template <int OP>
-constexpr bool kTileable = (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP>);
+// (5.0 vs 4.3) and the fp32 uniform fill (4.4-4.8 vs 4.1-4.4).  The normal fill spends too much
+// arithmetic per element to gain (4.3 vs 4.2), and the 16-bit fills lose (2.8 vs 3.5): they keep
+// the ragged kernel.
+template <int OP, int DT>
+constexpr bool kTileable =
+    (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP> || (OP == kOpUniform && DT == kF32));
 
 template <int OP, int DT, typename IT, int NOUT>
 hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
@@ -646,7 +648,7 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
     case kAligned:
       return enqueue(aligned_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
-      if constexpr (kTileable<OP>)
+      if constexpr (kTileable<OP, DT>)
         return enqueue(tiled_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm,
                        TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
                        mask);
@@ -696,7 +698,7 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   uint64_t tile_units = 0;
   if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0)) {
     flavour = kAligned;
-  } else if (rs.run_len >= 16 && kTileable<OP>) {
+  } else if (rs.run_len >= 16 && kTileable<OP, DT>) {
     tile_units = pick_tile_units(rs.run_len, V, rs.phases_equal);
     if (tile_units != 0) flavour = kTiled;
   }
