@@ -472,10 +472,16 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
         run_lo + static_cast<int32_t>(4 * bi) - static_cast<int32_t>(static_cast<uint32_t>(run_pos) & 3u);
     const int32_t lo = max(run_lo, 0);
     const int32_t hi = min(run_lo + static_cast<int32_t>(plan.run_len), lim);
-    const uint32_t width = static_cast<uint32_t>(hi - lo);  // hi > lo: the run intersects the tile
-    const uint32_t base = static_cast<uint32_t>(rel - lo);
+    if (rel >= lo && rel + 4 <= hi) {
+      // Interior block (nearly all of them): four writes off one address.
 #pragma unroll
-    for (int e = 0; e < 4; ++e) tile[(base + e < width) ? rel + e : kDummy] = v[e];
+      for (int e = 0; e < 4; ++e) tile[rel + e] = v[e];
+    } else {
+      const uint32_t width = static_cast<uint32_t>(hi - lo);  // hi > lo: the run intersects the tile
+      const uint32_t base = static_cast<uint32_t>(rel - lo);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tile[(base + e < width) ? rel + e : kDummy] = v[e];
+    }
   }
   __syncthreads();
 
@@ -624,9 +630,9 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 // ---- dispatch --------------------------------------------------------------------
 enum Flavour { kAligned, kTiled, kRagged };
 // Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
-// through LDS doubles the rate of bf16 dropout (4.7 vs 2.4 TB/s) and helps the raw fill
-// (5.0 vs 4.3) and the fp32 uniform fill (4.4-4.8 vs 4.1-4.4).  The normal fill spends too much
-// arithmetic per element to gain (4.3 vs 4.2), and the 16-bit fills lose (2.8 vs 3.5): they keep
+// through LDS doubles the rate of bf16 dropout (5.7 vs 2.4 TB/s) and helps the raw fill
+// (5.4 vs 4.3) and the fp32 uniform fill (5.1 vs 4.2).  The fp32 normal fill spends too much
+// arithmetic per element to gain (4.4 vs 4.3), and the 16-bit fills lose (3.0 vs 3.5): they keep
 // the ragged kernel.
 template <int OP, int DT>
 constexpr bool kTileable =
