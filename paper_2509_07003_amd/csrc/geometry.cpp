@@ -219,6 +219,9 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
     g->chain.local_shape[d] = length[static_cast<size_t>(d)];
     g->chain.stride[d] = pi[static_cast<size_t>(d)];
   }
+  g->chain.fits32 = (static_cast<uint64_t>(g->local_numel) >> 32) == 0 ? 1 : 0;
+  for (int d = 0; d < nd; ++d)
+    if ((static_cast<uint64_t>(s->global_shape[d]) >> 32) != 0) g->chain.fits32 = 0;
   g->global_numel = numel;
   g->max_global_index = max_index;
   g->origin = 0;

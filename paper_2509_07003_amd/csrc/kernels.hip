@@ -581,19 +581,25 @@ void fill_pointers(Tuple& values, void** ptrs, std::index_sequence<I...>) {
 // (lo32 q, hi32 q, lo32 tau, hi32 tau) with q = beta / 4, word beta mod 4.
 template <int OP, int DT>
 __global__ void __launch_bounds__(kThreads)
-chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, const uint64_t local_numel,
-             const OpParams prm, const void* xin, void* out, uint8_t* mask) {
+chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, const uint32_t theta32,
+             const uint32_t small, const uint64_t local_numel, const OpParams prm, const void* xin, void* out,
+             uint8_t* mask) {
   const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (i >= local_numel) return;
-  const uint64_t j = chain_global_index(cp, i);
-  uint32_t d[4], v[4];
+  // Wave-uniform choice: the common small plans (<= 4 dimensions, <= 2 placements each, 32-bit
+  // extents) take the unrolled map; anything else the general one.
+  const uint64_t j = small ? chain_global_index_fixed<4, 2, uint32_t>(cp, static_cast<uint32_t>(i))
+                           : chain_global_index(cp, i);
+  uint32_t d[4];
   uint32_t word;
   if (theta == 0) {
     const uint64_t p = offset + j;
     philox_block(p >> 2, prm.key0, prm.key1, d);
     word = static_cast<uint32_t>(p) & 3u;
   } else {
-    const uint64_t step = j / theta;
+    // theta32: theta and every global index are below 2^32, so the division can be a 32-bit one.
+    const uint64_t step = theta32 ? static_cast<uint64_t>(static_cast<uint32_t>(j) / static_cast<uint32_t>(theta))
+                                  : j / theta;
     const uint64_t tau = j - step * theta;
     const uint64_t beta = offset + step;
     const uint64_t q = beta >> 2;
@@ -601,8 +607,21 @@ chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, co
                   static_cast<uint32_t>(tau >> 32), prm.key0, prm.key1, d);
     word = static_cast<uint32_t>(beta) & 3u;
   }
-  convert_block<OP, DT>(d, prm, v);
-  const uint32_t value = word == 0u ? v[0] : word == 1u ? v[1] : word == 2u ? v[2] : v[3];
+  // Only one word of the block is this element's: pick the draw (for a normal, its pair) first
+  // and convert that alone.  The conversions are the ones convert_block applies.
+  uint32_t value;
+  if constexpr (OP == kOpNormal) {
+    const bool upper = (word & 2u) != 0u;
+    float even, odd;
+    normal_pair(upper ? d[2] : d[0], upper ? d[3] : d[1], prm, even, odd);
+    value = __float_as_uint((word & 1u) ? odd : even);
+  } else {
+    const uint32_t x = word == 0u ? d[0] : word == 1u ? d[1] : word == 2u ? d[2] : d[3];
+    if constexpr (OP == kOpUniform)
+      value = __float_as_uint(prm.unit_range ? uniform_unit<DT>(x, prm) : uniform_general(x, prm));
+    else
+      value = x;
+  }
   emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
 }
 
@@ -623,8 +642,12 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
   const uint64_t n = static_cast<uint64_t>(g.local_numel);
   const uint64_t blocks = (n + kThreads - 1) / kThreads;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  const uint32_t theta32 = ((g.virtual_threads | g.max_global_index) >> 32) == 0 ? 1u : 0u;
+  uint32_t small = (g.chain.fits32 && g.chain.ndim <= 4) ? 1u : 0u;
+  for (int d = 0; d < g.chain.ndim; ++d)
+    if (g.chain.nsteps[d] > 2) small = 0u;
   return enqueue(chain_kernel<OP, DT>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), stream, g.chain, offset,
-                 g.virtual_threads, n, prm, x, out, mask);
+                 g.virtual_threads, theta32, small, n, prm, x, out, mask);
 }
 
 // ---- dispatch --------------------------------------------------------------------

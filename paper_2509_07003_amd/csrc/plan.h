@@ -115,32 +115,78 @@ struct ChainStep {
 
 struct ChainPlan {
   int32_t ndim;
+  int32_t fits32;  // the local element count and every global extent are below 2^32
   int32_t nsteps[kMaxDims];
   int64_t local_shape[kMaxDims];
   int64_t stride[kMaxDims];  // global stride pi, in elements
   ChainStep steps[kMaxDims][kMaxSteps];
 };
 
-// Global flat index j of local flat index i.
-VESRNG_HD uint64_t chain_global_index(const ChainPlan& p, uint64_t i) {
+// Global flat index j of local flat index i.  T is the type the decode divides in: uint32_t
+// when p.fits32 (every coordinate then fits 32 bits; a 32-bit division costs a fifth of a
+// 64-bit one on the GPU), uint64_t otherwise.  The dot product with the stride is 64-bit.
+template <typename T>
+VESRNG_HD uint64_t chain_global_index_as(const ChainPlan& p, T i) {
   uint64_t j = 0;
   for (int d = p.ndim - 1; d >= 0; --d) {
-    const uint64_t n = static_cast<uint64_t>(p.local_shape[d]);
-    const uint64_t q = i / n;
-    int64_t c = static_cast<int64_t>(i - q * n);
+    const T n = static_cast<T>(p.local_shape[d]);
+    const T q = i / n;
+    T c = i - q * n;
     i = q;
     for (int m = p.nsteps[d] - 1; m >= 0; --m) {
       const ChainStep& st = p.steps[d][m];
       if (st.interleaved) {
-        const int64_t g = c / st.len;
-        c = g * st.per + st.start + (c - g * st.len);
+        const T len = static_cast<T>(st.len);
+        const T g = c / len;
+        c = g * static_cast<T>(st.per) + static_cast<T>(st.start) + (c - g * len);
       } else {
-        c += st.start;
+        c += static_cast<T>(st.start);
       }
     }
     j += static_cast<uint64_t>(c) * static_cast<uint64_t>(p.stride[d]);
   }
   return j;
+}
+
+// The same map with compile-time loop bounds (ndim <= ND, at most NS placements per dimension),
+// so that a kernel fetches the whole plan in one batch instead of one dependent scalar load
+// after another inside data-dependent loops.
+template <int ND, int NS, typename T>
+VESRNG_HD uint64_t chain_global_index_fixed(const ChainPlan& p, T i) {
+  uint64_t j = 0;
+#if defined(__HIPCC__)
+#pragma unroll
+#endif
+  for (int d = ND - 1; d >= 0; --d) {
+    if (d < p.ndim) {
+      const T n = static_cast<T>(p.local_shape[d]);
+      const T q = i / n;
+      T c = i - q * n;
+      i = q;
+#if defined(__HIPCC__)
+#pragma unroll
+#endif
+      for (int m = NS - 1; m >= 0; --m) {
+        if (m < p.nsteps[d]) {
+          const ChainStep& st = p.steps[d][m];
+          if (st.interleaved) {
+            const T len = static_cast<T>(st.len);
+            const T g = c / len;
+            c = g * static_cast<T>(st.per) + static_cast<T>(st.start) + (c - g * len);
+          } else {
+            c += static_cast<T>(st.start);
+          }
+        }
+      }
+      j += static_cast<uint64_t>(c) * static_cast<uint64_t>(p.stride[d]);
+    }
+  }
+  return j;
+}
+
+VESRNG_HD uint64_t chain_global_index(const ChainPlan& p, uint64_t i) {
+  return p.fits32 ? chain_global_index_as<uint32_t>(p, static_cast<uint32_t>(i))
+                  : chain_global_index_as<uint64_t>(p, i);
 }
 
 }  // namespace vesrng
