@@ -830,3 +830,75 @@ def test_concurrent_host_threads_on_their_own_streams():
     for k, want in enumerate(alone):
         for got in results[k]:
             assert got.tobytes() == want.tobytes(), jobs[k]
+
+
+def test_generator_sequence_of_operators_matches_one_device_doing_the_same_sequence():
+    """RNG-state progression over several operators: every rank of a 2 x 2 mesh runs the same
+    sequence of calls on differently sharded tensors with its own Generator; each shard equals the
+    oracle at the offset the sequence has reached, all ranks end on the same offset, and the merged
+    shards equal what ONE device produces with the same sequence on the unsharded tensors."""
+    mesh = [2, 2]
+    seq = [("uniform", "f32", [64, 48], [("S", 0), ("S", 1)]),
+           ("normal", "bf16", [33, 50], [("S", 1), ("R",)]),
+           ("randint", None, [7, 5, 6], [("R",), ("S", 2)]),
+           ("dropout", "f16", [40, 24], [("S", 0), ("S", 0)]),
+           ("raw", None, [96], [("IS", 0, 2), ("S", 0)])]
+    x_global = {k: W.f16_bits_from_f32(np.random.default_rng(k).standard_normal(int(np.prod(s[2])), dtype=np.float32)
+                                       ).reshape(s[2]) for k, s in enumerate(seq) if s[0] == "dropout"}
+
+    def run(mesh_shape, placements_of, coord):
+        g = v.Generator(seed=2468, offset=16)
+        outs, offsets = [], []
+        for k, (op, dt, shape, pls) in enumerate(seq):
+            args = (shape, mesh_shape, placements_of(pls), list(coord))
+            sh = v.Sharding(*args)
+            lshape, n = v.vesrng_local_shape(sh)
+            offsets.append(g.offset)
+            if op == "raw":
+                out = torch.empty(max(n, 1), dtype=torch.int32, device=DEV)
+                g.raw_u32_(sh, out)
+                res = out.cpu().numpy().view(np.uint32)
+            elif op == "randint":
+                out = torch.empty(max(n, 1), dtype=torch.int64, device=DEV)
+                g.randint_(sh, out, -5, 1000)
+                res = out.cpu().numpy()
+            elif op == "dropout":
+                idx = oracle.global_indices(*args).reshape(-1)
+                xs = x_global[k].reshape(-1)[idx.astype(np.int64)] if n else np.zeros(1, np.uint16)
+                xd = to_device(xs, dt)
+                y = torch.empty_like(xd)
+                g.dropout(sh, DT[dt][1], 0.25, xd, y, None)
+                res = to_host(y, dt)
+            else:
+                out = torch.empty(max(n, 1), dtype=DT[dt][0], device=DEV)
+                if op == "uniform":
+                    g.uniform_(sh, DT[dt][1], out, -1.0, 1.0)
+                else:
+                    g.normal_(sh, DT[dt][1], out, 0.5, 2.0)
+                res = to_host(out, dt)
+            torch.cuda.synchronize()
+            outs.append((res[:n].reshape(lshape), args))
+        return outs, offsets, g.offset
+
+    single, offs1, end1 = run([1], lambda pls: [("R",)], (0,))
+    per_rank = {c: run(mesh, lambda pls: pls, c) for c in mesh_coords(mesh)}
+    assert all(r[1] == offs1 and r[2] == end1 for r in per_rank.values())        # lockstep, no exchange
+    assert end1 == 16 + sum(4 * ((int(np.prod(s[2])) + 3) // 4) for s in seq)
+    for k, (op, dt, shape, pls) in enumerate(seq):
+        shards = {c: per_rank[c][0][k][0] for c in per_rank}
+        if op == "normal":   # the GPU's own normals are the same function of the global index on every shard
+            assert merge_shards(shards, mesh, pls).tobytes() == single[k][0].tobytes(), seq[k]
+            check_normal(single[k][0], single[k][1], dt, 0.5, 2.0, 2468, offs1[k], str(seq[k]))
+            continue
+        assert merge_shards(shards, mesh, pls).tobytes() == single[k][0].tobytes(), seq[k]
+        args = single[k][1]
+        if op == "uniform":
+            want = oracle.uniform(args, oracle.F32, -1.0, 1.0, 2468, offs1[k])
+            assert np.array_equal(single[k][0].view(np.uint32), want.view(np.uint32))
+        elif op == "randint":
+            assert np.array_equal(single[k][0], oracle.randint(args, -5, 1000, 2468, offs1[k]))
+        elif op == "raw":
+            assert np.array_equal(single[k][0], oracle.raw_u32(args, 2468, offs1[k]))
+        else:
+            want = oracle.dropout(args, oracle.F16, 0.25, 2468, offs1[k], x_global[k].reshape(-1))[0]
+            assert_float_bits_equal(single[k][0], want, str(seq[k]), dtype="f16")

@@ -292,3 +292,30 @@ def test_import_fails_loudly_without_the_native_library(tmp_path):
                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
     assert res.returncode != 0
     assert "hipcc failed" in res.stderr or "libvesrng" in res.stderr
+
+
+def test_generator_state_advances_by_the_global_tensor_on_every_rank():
+    """The caller-side (seed, offset) bookkeeping: the offset moves by what the operator consumes on
+    the GLOBAL tensor (the oracle's rule), identically for every rank and placement."""
+    tensors = [([1024, 1024], None), ([5], None), ([3, 3], None), ([4096, 4096], None), ([7, 9], [20, 2]), ([], None)]
+    want = 64
+    track = [want]
+    for shape, stride in tensors:
+        want = oracle.advance_offset(shape, want, stride)
+        track.append(want)
+    for mesh, pls_of, coords in (([1], lambda d: [("R",)], [(0,)]), ([4], lambda d: [("S", 0)] if d else [("R",)], [(0,), (3,)]),
+                                 ([2, 2], lambda d: [("S", d - 1), ("R",)] if d else [("R",), ("R",)], [(0, 1), (1, 0)])):
+        for coord in coords:
+            g = v.Generator(seed=9, offset=64)
+            seen = [g.offset]
+            for shape, stride in tensors:
+                g._advance(v.Sharding(shape, mesh, pls_of(len(shape)), list(coord), stride))
+                seen.append(g.offset)
+            assert seen == track, (mesh, coord)
+    g = v.Generator(1, 8)
+    g.set_state((5, 16))
+    assert g.get_state() == (5, 16)
+    with pytest.raises(ValueError):
+        v.Generator(1, 6)
+    with pytest.raises(ValueError):
+        g.set_state((1, 2))
