@@ -182,8 +182,20 @@ def steady_state(v, W, torch):
     return res
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(torch, W, w, coord, x_dev, sample):
-    """The oracle, as it stands, on the first `sample` elements of the same shard."""
+    """The oracle, as it stands, on the first `sample` elements of the same shard: all host threads
+    (the `value`), and one thread on a 32 times smaller sample."""
     import numpy as np
     import oracle
     threads = min(16, os.cpu_count() or 1)
@@ -194,9 +206,16 @@ def cpu_baseline(torch, W, w, coord, x_dev, sample):
     t0 = time.perf_counter()
     oracle.dropout(args, oracle.BF16, w.params["p"], w.seed, 0, xh, i_begin=0, i_end=sample, threads=threads)
     dt = time.perf_counter() - t0
+    one = max(1, sample // 32)
+    t0 = time.perf_counter()
+    oracle.dropout(args, oracle.BF16, w.params["p"], w.seed, 0, xh, i_begin=0, i_end=one, threads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": algorithmic_bytes(w.op, w.dtype, sample) / dt / 1e9, "unit": "GB/s", "cores": threads,
-            "kind": "oracle", "seconds": dt,
-            "sample": "first %d of %d elements of the same C5 shard (scalar C++ oracle, %d std::threads)" % (sample, n, threads)}
+            "kind": "oracle", "seconds": dt, "gsamples_per_s": sample / dt / 1e9,
+            "sample": "first %d of %d elements of the same C5 shard (scalar C++ oracle, %d std::threads)" % (sample, n, threads),
+            "single_thread": {"value": algorithmic_bytes(w.op, w.dtype, one) / dt1 / 1e9, "unit": "GB/s", "seconds": dt1,
+                              "gsamples_per_s": one / dt1 / 1e9, "sample": "first %d elements, 1 thread" % one},
+            "cpu_model": cpu_model(), "logical_cpus_visible": os.cpu_count()}
 
 
 def main():
