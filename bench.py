@@ -295,6 +295,16 @@ def main():
                       "gsamples_per_s": n / (wall / a.steps) / 1e9, "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
            "roofline": roofline}
 
+    props = torch.cuda.get_device_properties(0)
+    dev = {"name": props.name, "compute_units": props.multi_processor_count,
+           "hbm_gib": round(props.total_memory / 2 ** 30, 1)}
+    cus, sclk_khz, mem_khz, bus_bits = v.vesrng_device_info()
+    # HBM3E at 8 Gb/s per pin makes four transfers per reported memory clock (2 GHz on MI355X).
+    dev.update({"shader_clock_mhz": sclk_khz / 1e3, "memory_clock_mhz": mem_khz / 1e3, "memory_bus_bits": bus_bits,
+                "hbm_peak_at_4_transfers_per_clock_gb_per_s": 4 * mem_khz * 1e3 * bus_bits / 8 / 1e9,
+                "valu_lanes": cus * 4 * 16})
+    out["device"] = dev
+
     if a.calibrate_copy:
         for _ in range(3):
             y.copy_(x)   # reads 1 GiB, writes 1 GiB

@@ -187,6 +187,13 @@ typedef enum {
 VESRNG_API vesrng_status vesrng_probe(vesrng_probe_kind kind, uint64_t units, const void* in, void* out,
                                       void* out2, void* hip_stream);
 
+/* Measurement aid: what the HIP runtime reports for the current device, for the roofline's
+ * denominators.  Host pointers; any may be NULL.  On MI355X the runtime reports a memory clock
+ * of 2,000,000 kHz and a bus of 8192 bits: HBM3E's 8 Gb/s per pin is four transfers per reported
+ * clock, i.e. 4 * clock * bus / 8 = 8.19 TB/s, the published 8 TB/s. */
+VESRNG_API vesrng_status vesrng_device_info(int32_t* compute_units, int32_t* shader_clock_khz,
+                                            int32_t* memory_clock_khz, int32_t* memory_bus_bits);
+
 VESRNG_API const char* vesrng_status_string(vesrng_status st);
 
 #ifdef __cplusplus

@@ -47,6 +47,7 @@ def _load():
         "vesrng_dropout_add": [sp, i32, dbl, u64, u64, vp, vp, vp, vp, vp],
         "vesrng_randint": [sp, i64, i64, u64, u64, vp, vp],
         "vesrng_probe": [i32, u64, vp, vp, vp, vp],
+        "vesrng_device_info": [C.POINTER(i32)] * 4,
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)
@@ -192,6 +193,13 @@ PROBE_STORE, PROBE_COPY, PROBE_DROPOUT_TRAFFIC, PROBE_PHILOX = 0, 1, 2, 3
 
 def vesrng_probe(kind, units, src, out, out2=None, stream=None):
     _check(_lib.vesrng_probe(kind, units, _dev(src), _dev(out), _dev(out2), _stream(stream, src, out, out2)))
+
+
+def vesrng_device_info():
+    """(compute units, shader clock kHz, memory clock kHz, memory bus width in bits) of the current device."""
+    vals = [C.c_int32() for _ in range(4)]
+    _check(_lib.vesrng_device_info(*[C.byref(x) for x in vals]))
+    return tuple(x.value for x in vals)
 
 
 def vesrng_randint(sharding, low, high, seed, offset, out, stream=None):

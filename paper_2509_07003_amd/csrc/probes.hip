@@ -89,3 +89,23 @@ extern "C" vesrng_status vesrng_probe(vesrng_probe_kind kind, uint64_t units, co
   }
   return hipGetLastError() == hipSuccess ? VESRNG_OK : VESRNG_ERR_HIP;
 }
+
+extern "C" vesrng_status vesrng_device_info(int32_t* compute_units, int32_t* shader_clock_khz,
+                                            int32_t* memory_clock_khz, int32_t* memory_bus_bits) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return VESRNG_ERR_HIP;
+  const struct {
+    int32_t* where;
+    hipDeviceAttribute_t what;
+  } wanted[] = {{compute_units, hipDeviceAttributeMultiprocessorCount},
+                {shader_clock_khz, hipDeviceAttributeClockRate},
+                {memory_clock_khz, hipDeviceAttributeMemoryClockRate},
+                {memory_bus_bits, hipDeviceAttributeMemoryBusWidth}};
+  for (const auto& w : wanted) {
+    if (!w.where) continue;
+    int value = 0;
+    if (hipDeviceGetAttribute(&value, w.what, dev) != hipSuccess) return VESRNG_ERR_HIP;
+    *w.where = value;
+  }
+  return VESRNG_OK;
+}
