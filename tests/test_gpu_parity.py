@@ -624,7 +624,11 @@ def test_random_descriptions_all_kernel_flavours():
 
 
 def test_ceiling_probes_do_what_they_say():
-    """The measurement aids: store pattern, copy, dropout traffic pattern, generator-only."""
+    """The measurement aids: store pattern, copy, dropout traffic pattern, generator-only; and the
+    device properties the roofline's denominators come from."""
+    cus, shader_khz, memory_khz, bus_bits = v.vesrng_device_info()
+    assert cus == torch.cuda.get_device_properties(0).multi_processor_count
+    assert shader_khz > 0 and memory_khz > 0 and bus_bits >= 1024
     units = 4096 + 3
     a = torch.zeros(units * 4, dtype=torch.int32, device=DEV)
     v.vesrng_probe(v.PROBE_STORE, units, None, a)
