@@ -428,7 +428,9 @@ struct TileArgs {
   uint64_t local_numel;
 };
 
-template <int OP, int DT, typename IT, int NOUT>
+// UPT: aligned units a thread takes out of the tile in stage B (the tile is up to kThreads * UPT
+// units).
+template <int OP, int DT, typename IT, int NOUT, int UPT>
 __global__ void __launch_bounds__(kThreads)
 tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, const void* xin, void* out,
              uint8_t* mask) {
@@ -436,8 +438,8 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
   constexpr int V = UnitOf<OP, DT>::kElems;
   // One 32-bit value per local element of the tile, plus a slot that swallows the lanes of
   // edge blocks that fall outside the tile or the run (cheaper than predicated LDS writes).
-  constexpr int kDummy = kThreads * V;
-  __shared__ __attribute__((aligned(16))) uint32_t tile[kThreads * V + 4];
+  constexpr int kDummy = kThreads * V * UPT;
+  __shared__ __attribute__((aligned(16))) uint32_t tile[kThreads * V * UPT + 4];
 
   const uint64_t tile_elems = static_cast<uint64_t>(ta.tile_units) * V;
   const uint64_t i0 = static_cast<uint64_t>(blockIdx.x) * tile_elems;  // first local element of the tile
@@ -499,25 +501,27 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
     }
     return;
   }
-  const uint64_t u = static_cast<uint64_t>(blockIdx.x) * ta.tile_units + threadIdx.x;
-  const uint64_t e0 = u * V;
-  if (threadIdx.x >= ta.tile_units || e0 >= i1) return;
-  if (e0 + V <= i1) {
-    uint32_t v[V];
+  for (uint32_t t = threadIdx.x; t < ta.tile_units; t += kThreads) {
+    const uint64_t u = static_cast<uint64_t>(blockIdx.x) * ta.tile_units + t;
+    const uint64_t e0 = u * V;
+    if (e0 >= i1) break;
+    if (e0 + V <= i1) {
+      uint32_t v[V];
 #pragma unroll
-    for (int q = 0; q < V / 4; ++q) {
-      const u32x4 t = *reinterpret_cast<const u32x4*>(&tile[threadIdx.x * V + 4 * q]);
+      for (int q = 0; q < V / 4; ++q) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(&tile[t * V + 4 * q]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[4 * q + e] = t[e];
+        for (int e = 0; e < 4; ++e) v[4 * q + e] = w[e];
+      }
+      u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
+      if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
+      if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + u);
+      emit_unit<OP, DT>(v, prm, xv, rv, u, out, mask);
+    } else {
+      // The last unit of a shard whose size is not a multiple of the unit.
+      for (uint64_t i = e0; i < i1; ++i)
+        emit_element<OP, DT>(tile[i - i0], prm, xin, static_cast<int64_t>(i), out, mask);
     }
-    u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
-    if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
-    if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + u);
-    emit_unit<OP, DT>(v, prm, xv, rv, u, out, mask);
-  } else {
-    // The last unit of a shard whose size is not a multiple of the unit.
-    for (uint64_t i = e0; i < i1; ++i)
-      emit_element<OP, DT>(tile[i - i0], prm, xin, static_cast<int64_t>(i), out, mask);
   }
 }
 
@@ -651,22 +655,33 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 }
 
 // ---- dispatch --------------------------------------------------------------------
-enum Flavour { kAligned, kTiled, kRagged };
+enum Flavour { kAligned, kTiled, kTiledBig, kRagged };
 // Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
-// through LDS doubles the rate of bf16 dropout (5.7 vs 2.4 TB/s) and helps the raw fill
-// (5.4 vs 4.3) and the fp32 uniform fill (5.1 vs 4.2).  The fp32 normal fill spends too much
-// arithmetic per element to gain (4.4 vs 4.3), and the 16-bit fills lose (3.0 vs 3.5): they keep
-// the ragged kernel.
+// through LDS doubles the rate of bf16 dropout (5.8 vs 2.4 TB/s) and helps the raw fill
+// (5.4 vs 4.3), the fp32 uniform fill (5.1 vs 4.2) and randint.  The 16-bit fills lose (3.0 vs
+// 3.5) and keep the ragged kernel.
 template <int OP, int DT>
 constexpr bool kTileable =
     (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP> || (OP == kOpUniform && DT == kF32));
+// The tiled kernel is bound by the latency of a workgroup's life, not by arithmetic or LDS, so
+// on LARGE shards the write-only fp32 fills gain from four units per thread (raw 5.4 -> 5.9,
+// uniform 5.1 -> 5.6, normal 4.2 (ragged kernel) -> 4.7 TB/s); on small shards the four times
+// fewer workgroups no longer fill the chip (a 22 MB normal fill: 9.0 vs 7.9 us).  Dropout and
+// randint, which issue more memory instructions per unit, lose (dropout fp32 6.25 -> 5.8,
+// randint 5.85 -> 5.1) and keep one unit.
+template <int OP, int DT>
+constexpr bool kBigTileable = ((OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) && UnitOf<OP, DT>::kElems == 4);
+// Smallest shard that takes the big tile (measured crossover: 2^24 elements, 2^26 for the normal fill).
+template <int OP>
+constexpr uint64_t kBigTileMinElems = (OP == kOpNormal) ? (1ull << 26) : (1ull << 24);
+constexpr int kBigTileUnits = 4;
 
 template <int OP, int DT, typename IT, int NOUT>
 hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
                        const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
   constexpr uint64_t V = UnitOf<OP, DT>::kElems;
   uint64_t blocks;
-  if (flavour == kTiled)
+  if (flavour == kTiled || flavour == kTiledBig)
     blocks = (local_numel + tile_units * V - 1) / (tile_units * V);
   else
     blocks = (plan.total_units + kThreads - 1) / kThreads;
@@ -678,7 +693,13 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
       return enqueue(aligned_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
       if constexpr (kTileable<OP, DT>)
-        return enqueue(tiled_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm,
+        return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1>, grid, block, stream, plan, prm,
+                       TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
+                       mask);
+      break;
+    case kTiledBig:
+      if constexpr (kBigTileable<OP, DT>)
+        return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits>, grid, block, stream, plan, prm,
                        TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
                        mask);
       break;
@@ -705,9 +726,9 @@ hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, 
 // generator blocks fit `passes` rounds of the workgroup: a tile of T elements cut by B run
 // boundaries touches at most T/4 + 1.5 (B + 1) blocks, plus one dead slot per boundary when
 // runs differ in phase.  0 = runs too short for tiling.
-uint64_t pick_tile_units(uint64_t run_len, uint64_t V, bool phases_equal) {
-  const uint64_t passes = V / 4;
-  for (uint64_t q = kThreads; q >= 32; q -= 8) {
+uint64_t pick_tile_units(uint64_t run_len, uint64_t V, uint64_t per_thread, bool phases_equal) {
+  const uint64_t passes = V / 4 * per_thread;
+  for (uint64_t q = kThreads * per_thread; q >= 32; q -= 8) {
     const uint64_t t = q * V;
     const uint64_t b = (t + run_len - 1) / run_len;
     const uint64_t blocks = t / 4 + (3 * (b + 1) + 1) / 2 + (phases_equal ? 0 : b) + 1;
@@ -727,9 +748,15 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   uint64_t tile_units = 0;
   if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0)) {
     flavour = kAligned;
-  } else if (rs.run_len >= 16 && kTileable<OP, DT>) {
-    tile_units = pick_tile_units(rs.run_len, V, rs.phases_equal);
-    if (tile_units != 0) flavour = kTiled;
+  } else if (rs.run_len >= 16) {
+    if (kBigTileable<OP, DT> && static_cast<uint64_t>(g.local_numel) >= kBigTileMinElems<OP>) {
+      tile_units = pick_tile_units(rs.run_len, V, kBigTileUnits, rs.phases_equal);
+      if (tile_units != 0) flavour = kTiledBig;
+    }
+    if (flavour == kRagged && kTileable<OP, DT>) {
+      tile_units = pick_tile_units(rs.run_len, V, 1, rs.phases_equal);
+      if (tile_units != 0) flavour = kTiled;
+    }
   }
   // Aligned: units of V elements.  Otherwise: one unit per generator block a run can touch;
   // with unequal phases the count is the upper bound over phases 0..3.

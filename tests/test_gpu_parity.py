@@ -906,3 +906,28 @@ def test_generator_sequence_of_operators_matches_one_device_doing_the_same_seque
         else:
             want = oracle.dropout(args, oracle.F16, 0.25, 2468, offs1[k], x_global[k].reshape(-1))[0]
             assert_float_bits_equal(single[k][0], want, str(seq[k]), dtype="f16")
+
+
+def test_large_ragged_fp32_fills():
+    """Ragged column shards big enough (2^24 elements, 2^26 for the normal fill) to take the large-tile
+    form of the staging kernel: raw, uniform and normal fp32 against the threaded oracle, with the
+    rows' phases equal (row length 4100) and unequal (4101)."""
+    seed, offset = 31337, 1 << 33
+    for cols in (4100, 4101):
+        args = ([16384, cols], [3], [("S", 1)], [1])
+        n = oracle.local_shape(*args)[1]
+        assert n >= 1 << 24
+        say("large ragged %s" % (args,))
+        got = gpu_fill("raw", None, args, seed, offset)
+        assert np.array_equal(got, oracle.raw_u32(args, seed, offset, threads=THREADS)), args
+        for low, high in ((0.0, 1.0), (-2.0, 3.0)):
+            got = gpu_fill("uniform", "f32", args, seed, offset, low=low, high=high)
+            want = oracle.uniform(args, oracle.F32, low, high, seed, offset, threads=THREADS)
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (args, low, high)
+        del got, want
+        args = ([49152, cols], [3], [("S", 1)], [2])
+        assert oracle.local_shape(*args)[1] >= 1 << 26
+        say("large ragged %s" % (args,))
+        got = gpu_fill("normal", "f32", args, seed, offset, mean=-1.0, std=3.0)
+        check_normal(got, args, "f32", -1.0, 3.0, seed, offset, "normal f32 %s" % (args,))
+        del got
