@@ -8,7 +8,8 @@
 //
 //  * aligned kernels: every run of the shard starts on a block boundary and its
 //    length is a multiple of the unit (4 or 8 elements); unit w covers local
-//    elements [w*V, (w+1)*V) and all accesses are 16-byte vectors.
+//    elements [w*V, (w+1)*V) and all accesses are 16-byte vectors.  A shard that is
+//    a single run may have any length: its last, partial unit is written by element.
 //  * ragged kernels: any run start / length (e.g. a column shard whose first
 //    column is 1366).  A thread owns one GLOBAL block and stores the lanes that
 //    fall inside the run; whole blocks leave as one element-aligned vector store.
@@ -372,10 +373,21 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   locate<NOUT>(plan, w, run, unit, run_pos);
   const uint64_t block0 = (run_pos + static_cast<uint64_t>(unit) * V) >> 2;
 
+  // A shard that is ONE run (contiguous in the global tensor) may end inside a unit: its last
+  // unit is then written element by element, and its 16-byte load would pass the end of x.
+  bool partial = false;
+  uint32_t tail = 0;
+  if constexpr (NOUT == 0) {
+    tail = static_cast<uint32_t>(plan.run_len) & static_cast<uint32_t>(V - 1);
+    partial = tail != 0u && w64 + 1 == plan.total_units;
+  }
+
   // Dropout: issue the load before the generator so that it overlaps the ALU work.
   u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
-  if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + w64);
-  if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + w64);
+  if constexpr (kIsDropout<OP>)
+    if (!partial) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + w64);
+  if constexpr (OP == kOpDropoutAdd)
+    if (!partial) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + w64);
   __builtin_amdgcn_sched_barrier(0);  // the loads are issued here, not moved down to their first use
 
   uint32_t d[NB][4];
@@ -413,6 +425,13 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
     convert_block<OP, DT>(d[b], prm, vb);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[4 * b + e] = vb[e];
+  }
+  if (partial) {
+#pragma unroll
+    for (int e = 0; e < V - 1; ++e)
+      if (static_cast<uint32_t>(e) < tail)
+        emit_element<OP, DT>(v[e], prm, xin, static_cast<int64_t>(w64 * V + e), out, mask);
+    return;
   }
   emit_unit<OP, DT>(v, prm, xv, rv, w64, out, mask);
 }
@@ -746,7 +765,10 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   const uint64_t pos0 = offset + g.origin;
   Flavour flavour = kRagged;
   uint64_t tile_units = 0;
-  if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0)) {
+  // Aligned: every run starts on a block boundary and is whole units long - or the shard is a
+  // single run, whose last unit the aligned kernel finishes element by element (not randint,
+  // whose lanes trade halves of whole blocks).
+  if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0 || (rs.n_runs == 1 && OP != kOpRandint))) {
     flavour = kAligned;
   } else if (rs.run_len >= 16) {
     if (kBigTileable<OP, DT> && static_cast<uint64_t>(g.local_numel) >= kBigTileMinElems<OP>) {
@@ -761,7 +783,7 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   // Aligned: units of V elements.  Otherwise: one unit per generator block a run can touch;
   // with unequal phases the count is the upper bound over phases 0..3.
   const uint64_t phase_max = rs.phases_equal ? (pos0 % 4) : 3;
-  const uint64_t units = flavour == kAligned ? rs.run_len / V : (phase_max + rs.run_len + 3) / 4;
+  const uint64_t units = flavour == kAligned ? (rs.run_len + V - 1) / V : (phase_max + rs.run_len + 3) / 4;
   if (fits_32bit(rs, units))
     return launch_typed<OP, DT, uint32_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
   return launch_typed<OP, DT, uint64_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);

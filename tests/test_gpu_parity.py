@@ -931,3 +931,38 @@ def test_large_ragged_fp32_fills():
         got = gpu_fill("normal", "f32", args, seed, offset, mean=-1.0, std=3.0)
         check_normal(got, args, "f32", -1.0, 3.0, seed, offset, "normal f32 %s" % (args,))
         del got
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_contiguous_shards_of_any_length(dtype):
+    """A shard that is one contiguous run takes the vector kernel whatever its length; the last,
+    partial unit is finished element by element.  Unsharded tensors and row shards of odd sizes,
+    every floating-point operator."""
+    seed, offset = 555, 40
+    cases = [([n], [1], [("R",)], [0]) for n in (1, 2, 3, 5, 7, 9, 15, 17, 1001, 65543)]
+    cases += [([7, 11, 13], [1], [("R",)], [0]), ([9, 1001], [2], [("S", 0)], [1]), ([5, 3, 7], [3], [("S", 0)], [2])]
+    for args in cases:
+        n = oracle.local_shape(*args)[1]
+        got = gpu_fill("uniform", dtype, args, seed, offset, low=-1.0, high=2.0)
+        want = oracle.uniform(args, DT[dtype][2], -1.0, 2.0, seed, offset)
+        assert_float_bits_equal(got, want, "uniform %s %s" % (dtype, args), dtype=dtype)
+        got = gpu_fill("normal", dtype, args, seed, offset, mean=1.0, std=0.5)
+        check_normal(got, args, dtype, 1.0, 0.5, seed, offset, "normal %s %s" % (dtype, args))
+        xf = W.adversarial_f32(n, seed=n)
+        x = xf if dtype == "f32" else W.bits16_from_f32(xf, dtype)
+        yo, mo = oracle.dropout(args, DT[dtype][2], 0.3, seed, offset, x)
+        y, m = gpu_dropout(dtype, args, 0.3, seed, offset, x)
+        assert np.array_equal(m, mo), (dtype, args)
+        assert_float_bits_equal(y, yo, "dropout %s %s" % (dtype, args), dtype=dtype)
+        y, _ = gpu_dropout(dtype, args, 0.3, seed, offset, x, with_mask=False, in_place=True)
+        assert_float_bits_equal(y, yo, "dropout in place %s %s" % (dtype, args), dtype=dtype)
+        r = xf[::-1].copy() if dtype == "f32" else W.bits16_from_f32(xf[::-1].copy(), dtype)
+        yo, mo = oracle.dropout_add(args, DT[dtype][2], 0.3, seed, offset, x, r)
+        sh = v.Sharding(*args)
+        xd, rd = to_device(x, dtype), to_device(r, dtype)
+        yd = torch.empty_like(xd)
+        md = torch.empty(n, dtype=torch.uint8, device=DEV)
+        v.vesrng_dropout_add(sh, DT[dtype][1], 0.3, seed, offset, xd, rd, yd, md)
+        torch.cuda.synchronize()
+        assert np.array_equal(md.cpu().numpy().reshape(mo.shape), mo), (dtype, args)
+        assert_float_bits_equal(to_host(yd, dtype).reshape(yo.shape), yo, "dropout_add %s %s" % (dtype, args), dtype=dtype)
