@@ -262,7 +262,7 @@ def _grid_cases():
 
 @pytest.mark.parametrize("op,dtype", [("raw", None), ("uniform", "f32"), ("uniform", "bf16"), ("normal", "f32"),
                                        ("normal", "bf16"), ("dropout", "f32"), ("dropout", "bf16"),
-                                       ("randint", None)])
+                                       ("randint", None), ("uniform", "f16"), ("normal", "f16"), ("dropout", "f16")])
 def test_operator_matrix_1d_to_5d_single_and_double_sharding(op, dtype):
     """Scaled version of the paper's per-operator table: every operator, 1-D to 5-D tensors,
     sharding on every dimension and every ordered pair of dimensions, odd extents."""
@@ -281,19 +281,19 @@ def test_operator_matrix_1d_to_5d_single_and_double_sharding(op, dtype):
                 assert np.array_equal(got, oracle.randint(targs, -5, 1000003, seed, offset)), what
             elif op == "uniform":
                 got = gpu_fill("uniform", dtype, args, seed, offset, low=-2.5, high=7.25)
-                want = oracle.uniform(targs, oracle.F32 if dtype == "f32" else oracle.BF16, -2.5, 7.25, seed, offset)
-                assert_float_bits_equal(got, want, what)
+                want = oracle.uniform(targs, DT[dtype][2], -2.5, 7.25, seed, offset)
+                assert_float_bits_equal(got, want, what, dtype=dtype)
             elif op == "normal":
                 got = gpu_fill("normal", dtype, args, seed, offset, mean=1.5, std=0.25)
                 check_normal(got, args, dtype, 1.5, 0.25, seed, offset, what)
             else:
                 n = oracle.local_shape(*args)[1]
                 xf = W.adversarial_f32(n, seed=count)
-                x = xf if dtype == "f32" else W.bf16_bits_from_f32(xf)
+                x = xf if dtype == "f32" else W.bits16_from_f32(xf, dtype)
                 y, m = gpu_dropout(dtype, args, 0.3, seed, offset, x)
-                yo, mo = oracle.dropout(targs, oracle.F32 if dtype == "f32" else oracle.BF16, 0.3, seed, offset, x)
+                yo, mo = oracle.dropout(targs, DT[dtype][2], 0.3, seed, offset, x)
                 assert np.array_equal(m, mo), what
-                assert_float_bits_equal(y, yo, what)
+                assert_float_bits_equal(y, yo, what, dtype=dtype)
             count += 1
     assert count > 300
 
