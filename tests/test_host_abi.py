@@ -319,3 +319,12 @@ def test_generator_state_advances_by_the_global_tensor_on_every_rank():
         v.Generator(1, 6)
     with pytest.raises(ValueError):
         g.set_state((1, 2))
+
+
+def test_library_carries_gfx950_device_code_only():
+    """The in-tree library is built for MI355X: its device code object names gfx950 and no other GPU."""
+    import re
+    with open(v.library_path(), "rb") as f:
+        blob = f.read()
+    targets = set(re.findall(rb"amdgcn-amd-amdhsa--(gfx[0-9a-f]+)", blob))
+    assert targets == {b"gfx950"}, targets
