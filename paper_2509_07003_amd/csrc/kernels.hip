@@ -36,6 +36,7 @@
 #include "launch.hpp"
 #include "philox.h"
 #include "plan.h"
+#include "stream_store.h"
 
 namespace vesrng {
 
@@ -185,7 +186,7 @@ __device__ __forceinline__ void store_randint_pair(uint32_t x0, uint32_t x1, con
   const uint64_t r1 = static_cast<uint64_t>(randint_value(x1, prm));
   const u32x4 o = {static_cast<uint32_t>(r0), static_cast<uint32_t>(r0 >> 32), static_cast<uint32_t>(r1),
                    static_cast<uint32_t>(r1 >> 32)};
-  __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + c);
+  stream_store(o, static_cast<u32x4*>(out) + c);
 }
 
 // Writes unit number `u` of the local tensor (elements [u*V, (u+1)*V)) from the V values
@@ -210,8 +211,8 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
         y[e] = __float_as_uint(kAdd ? __fadd_rn(__uint_as_float(rv[e]), kept) : kept);
         m |= (keep ? 1u : 0u) << (8 * e);
       }
-      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + u);
-      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<uint32_t*>(mask) + u);
+      stream_store(y, static_cast<u32x4*>(out) + u);
+      if (mask) stream_store(m, reinterpret_cast<uint32_t*>(mask) + u);
     } else {
       u32x2 m = {0u, 0u};
 #pragma unroll
@@ -232,8 +233,8 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
           m[b] |= ((k0 ? 1u : 0u) | (k1 ? 0x100u : 0u)) << (16 * h);
         }
       }
-      __builtin_nontemporal_store(y, static_cast<u32x4*>(out) + u);
-      if (mask) __builtin_nontemporal_store(m, reinterpret_cast<u32x2*>(mask) + u);
+      stream_store(y, static_cast<u32x4*>(out) + u);
+      if (mask) stream_store(m, reinterpret_cast<u32x2*>(mask) + u);
     }
   } else {
     u32x4 o;
@@ -247,7 +248,7 @@ __device__ __forceinline__ void emit_unit(const uint32_t (&v)[UnitOf<OP, DT>::kE
         o[q] = pack16<DT>(a, b);
       }
     }
-    __builtin_nontemporal_store(o, static_cast<u32x4*>(out) + u);
+    stream_store(o, static_cast<u32x4*>(out) + u);
   }
 }
 

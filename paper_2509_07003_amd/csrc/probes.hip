@@ -6,6 +6,7 @@
 
 #include "../../include/vesrng.h"
 #include "philox.h"
+#include "stream_store.h"
 
 namespace {
 
@@ -13,20 +14,20 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kThreads = 256;
 
-// One 16-byte non-temporal store per thread.
+// One 16-byte streaming store per thread (the kernels' own store form).
 __global__ void __launch_bounds__(kThreads) store_probe(u32x4* out, uint64_t units) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (t >= units) return;
   const uint32_t v = static_cast<uint32_t>(t);
   const u32x4 q = {v, v + 1u, v + 2u, v + 3u};
-  __builtin_nontemporal_store(q, out + t);
+  vesrng::stream_store(q, out + t);
 }
 
 // 16 bytes in, 16 bytes out per thread.
 __global__ void __launch_bounds__(kThreads) copy_probe(const u32x4* in, u32x4* out, uint64_t units) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (t >= units) return;
-  __builtin_nontemporal_store(__builtin_nontemporal_load(in + t), out + t);
+  vesrng::stream_store(__builtin_nontemporal_load(in + t), out + t);
 }
 
 // The bf16 dropout kernel's accesses with no arithmetic: 16 bytes in, 16 + 8 bytes out per thread.
@@ -36,8 +37,8 @@ dropout_traffic_probe(const u32x4* in, u32x4* out, u32x2* mask, uint64_t units) 
   if (t >= units) return;
   const u32x4 v = __builtin_nontemporal_load(in + t);
   const u32x2 m = {v[0] & 0x01010101u, v[1] & 0x01010101u};
-  __builtin_nontemporal_store(v, out + t);
-  __builtin_nontemporal_store(m, mask + t);
+  vesrng::stream_store(v, out + t);
+  vesrng::stream_store(m, mask + t);
 }
 
 // Philox4x32-10 blocks and nothing else (the results are folded and, in practice, never stored).
