@@ -574,13 +574,13 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
   if constexpr (OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) {
     if (s.first == 0u && s.last == 4u) {
       if constexpr (OP == kOpRaw || DT == kF32) {
-        *reinterpret_cast<u32x4_align4*>(static_cast<uint32_t*>(out) + li0) = u32x4{v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<u32x4_align4*>(static_cast<uint32_t*>(out) + li0));
         return;
       } else if ((li0 & 1) == 0) {
         const float a = __uint_as_float(v[0]), b = __uint_as_float(v[1]);
         const float c = __uint_as_float(v[2]), e = __uint_as_float(v[3]);
         const uint32_t p01 = pack16<DT>(a, b), p23 = pack16<DT>(c, e);
-        *reinterpret_cast<u32x2_align4*>(static_cast<uint16_t*>(out) + li0) = u32x2{p01, p23};
+        __builtin_nontemporal_store(u32x2{p01, p23}, reinterpret_cast<u32x2_align4*>(static_cast<uint16_t*>(out) + li0));
         return;
       }
     }
