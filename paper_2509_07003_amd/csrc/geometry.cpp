@@ -180,7 +180,8 @@ vesrng_status build_geometry(const vesrng_sharding* s, Geometry* g) {
     boxes[static_cast<size_t>(d)].subs.assign(1, Sub{s->global_shape[d], 1});
     length[static_cast<size_t>(d)] = s->global_shape[d];
   }
-  g->virtual_threads = s->virtual_threads;
+  // One virtual thread is the flat stream itself (tau = 0, beta = offset + j): the fast kernels serve it.
+  g->virtual_threads = s->virtual_threads == 1 ? 0 : s->virtual_threads;
   g->boxed = true;
   g->chain = ChainPlan{};
   g->chain.ndim = nd;
