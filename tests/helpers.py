@@ -9,6 +9,11 @@ def mesh_coords(mesh_shape):
     return list(itertools.product(*[range(p) for p in mesh_shape]))
 
 
+class NotGatherable(Exception):
+    """The shards cannot be put back together by plain concatenation: an interleaved piece whose
+    length is not a whole number of groups (interleave over an uneven split)."""
+
+
 def merge_shards(shards, mesh_shape, placements):
     """Rebuilds the global array from {mesh_coord: local array} the way a sharded
     tensor is gathered: along each mesh dimension (innermost first) the ranks'
@@ -31,7 +36,8 @@ def merge_shards(shards, mesh_shape, placements):
             out = []
             for g in range(groups):
                 for p in parts:
-                    assert p.shape[d] % groups == 0
+                    if p.shape[d] % groups != 0:
+                        raise NotGatherable("%s over pieces of length %d" % (pl, p.shape[d]))
                     out.append(np.split(p, groups, axis=d)[g])
             return np.concatenate(out, axis=d)
         raise AssertionError(pl)

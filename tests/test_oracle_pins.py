@@ -12,7 +12,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import all_placements, merge_shards, mesh_coords
+from helpers import NotGatherable, all_placements, merge_shards, mesh_coords
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -180,11 +180,9 @@ def test_merge_invariant_brute_force():
                     continue
                 shards = {c: oracle.raw_u32((shape, mesh, list(pls), list(c)), seed, offset)
                           for c in mesh_coords(mesh)}
-                try:
-                    merged = merge_shards(shards, mesh, pls)
-                except AssertionError:
-                    # Interleave over an uneven split is not gatherable by plain concatenation.
-                    continue
+                # Nothing is caught here: replicas that differ, or pieces that do not fit together,
+                # fail the test (every valid case of this grid can be gathered by concatenation).
+                merged = merge_shards(shards, mesh, pls)
                 assert merged.shape == tuple(shape), (shape, mesh, pls)
                 assert np.array_equal(merged, single), (shape, mesh, pls)
                 checked += 1
@@ -207,6 +205,19 @@ def test_merge_invariant_has_teeth_against_per_rank_seed_and_offset():
     assert not np.array_equal(merge_shards(per_rank_off, [2], pls2), single2)
     good = {(r,): oracle.raw_u32((shape2, [2], pls2, [r]), 1, 0) for r in range(2)}
     assert np.array_equal(merge_shards(good, [2], pls2), single2)
+
+
+def test_merge_refuses_replicas_that_differ_and_pieces_that_do_not_fit():
+    """The merge used by the invariant tests must itself fail on what the invariant forbids."""
+    good = {(r,): oracle.raw_u32(([6], [2], [("R",)], [r]), 1, 0) for r in range(2)}
+    assert np.array_equal(merge_shards(good, [2], [("R",)]), good[(0,)])
+    bad = dict(good)
+    bad[(1,)] = bad[(1,)].copy()
+    bad[(1,)][3] ^= 1
+    with pytest.raises(AssertionError, match="replicas differ"):
+        merge_shards(bad, [2], [("R",)])
+    with pytest.raises(NotGatherable):
+        merge_shards({(0,): np.arange(3), (1,): np.arange(3)}, [2], [("IS", 0, 2)])
 
 
 def test_values_do_not_depend_on_the_sharding():
@@ -242,6 +253,52 @@ def test_offset_additivity_and_progression():
 def test_global_stride_changes_only_the_index_map():
     j = oracle.global_indices([3, 4], [1], [("R",)], [0], global_stride=[1, 3])
     assert np.array_equal(j, (np.arange(3)[:, None] + 3 * np.arange(4)[None, :]).astype(np.uint64))
+
+
+def test_offset_advance_under_a_global_stride_hand_worked():
+    """Section 5, design (f): every rank steps to the next global offset.  Under a non-contiguous
+    global view the operator reaches stream positions up to the LAST global flat index, so the
+    step is that index + 1 rounded up to a whole block.  Hand-worked:
+      [30,36] rows padded to 40: last index 29*40 + 35 = 1195 -> 1196 positions (1080 elements);
+      [3,5] with strides [7,1]:  last index 2*7 + 4 = 18 -> 19 -> 20;
+      [3,4] transposed [1,3]:    last index 2 + 9 = 11 -> 12;
+      [6,10,12] strides [1,6,60]: last 5 + 54 + 660 = 719 -> 720;
+      [2,3] strides [100,7]:     last 100 + 14 = 114 -> 115 -> 116 (6 elements);
+      the last one with 5 virtual threads: ceil(115 / 5) = 23 steps -> 24."""
+    assert oracle.advance_offset([30, 36], 0, [40, 1]) == 1196
+    assert oracle.advance_offset([30, 36], 64, [40, 1]) == 64 + 1196
+    assert oracle.advance_offset([3, 5], 8, [7, 1]) == 8 + 20
+    assert oracle.advance_offset([3, 4], 0, [1, 3]) == 12
+    assert oracle.advance_offset([6, 10, 12], 4, [1, 6, 60]) == 4 + 720
+    assert oracle.advance_offset([2, 3], 0, [100, 7]) == 116
+    assert oracle.advance_offset([2, 3], 0, [100, 7], 5) == 24
+    assert oracle.advance_offset([0, 3], 8, [100, 7]) == 8          # empty tensor: nothing consumed
+    # The invariant the rule exists for: the next operator's positions start beyond every position
+    # this one used, on every rank, and the step does not depend on the sharding.
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        nd = int(rng.integers(1, 4))
+        shape = [int(v) for v in rng.integers(1, 7, size=nd)]
+        order = list(rng.permutation(nd))
+        stride, acc = [0] * nd, 1
+        for d in order:
+            stride[d] = acc
+            acc *= shape[d] + int(rng.integers(0, 3))
+        off = 4 * int(rng.integers(0, 100))
+        nxt = oracle.advance_offset(shape, off, stride)
+        j = oracle.global_indices(shape, [1], [("R",)], [0], global_stride=stride)
+        assert nxt % 4 == 0 and off + int(j.max()) < nxt <= off + int(j.max()) + 4
+
+
+def test_randint_hand_worked_values():
+    """Integers worked by hand from the golden generator words (tests/golden/worked_randint.txt)."""
+    rows = _lines("worked_randint.txt")
+    assert len(rows) >= 40
+    for row in rows:
+        lhs, rhs = row.split("->")
+        seed, offset, j, low, high = [int(t) for t in lhs.split()]
+        got = oracle.randint(([j + 1], [1], [("R",)], [0]), low, high, seed, offset, i_begin=j)
+        assert int(got[j]) == int(rhs), row
 
 
 def test_invalid_descriptions_are_rejected():
