@@ -130,7 +130,7 @@ def time_graph(torch, launch, reps):
     return sorted(times)[len(times) // 2]
 
 
-def measured_ceilings(v, torch):
+def measured_ceilings(B, torch):
     """Rates of the plain probe kernels on this machine, in this run: what bare 128-bit stores,
     a 16-byte copy, the dropout kernel's access pattern without arithmetic, and the generator
     alone can reach.  1 GiB buffers (beyond the 256 MB last-level cache)."""
@@ -144,14 +144,14 @@ def measured_ceilings(v, torch):
     def med(fn):
         return time_kernel(torch, lambda _k: fn(), 20, 3)[1] * 1e-3
 
-    t_store = med(lambda: v.vesrng_probe(v.PROBE_STORE, units, None, a))
-    t_copy = med(lambda: v.vesrng_probe(v.PROBE_COPY, units, a, b))
-    t_mix = med(lambda: v.vesrng_probe(v.PROBE_DROPOUT_TRAFFIC, units, a, b, m))
-    t_gen = med(lambda: v.vesrng_probe(v.PROBE_PHILOX, blocks, None, a))
+    t_store = med(lambda: B.vesrng_bench_probe(B.PROBE_STORE, units, None, a))
+    t_copy = med(lambda: B.vesrng_bench_probe(B.PROBE_COPY, units, a, b))
+    t_mix = med(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m))
+    t_gen = med(lambda: B.vesrng_bench_probe(B.PROBE_PHILOX, blocks, None, a))
     return {"store_only_gb_per_s": nbytes / t_store / 1e9, "copy_gb_per_s": 2 * nbytes / t_copy / 1e9,
             "dropout_traffic_gb_per_s": 2.5 * nbytes / t_mix / 1e9,
             "philox_only_gblocks_per_s": blocks / t_gen / 1e9,
-            "note": "plain probe kernels of the library (vesrng_probe), medians of 20 launches in this run"}
+            "note": "plain probe kernels of libvesrng_bench.so (vesrng_bench_probe), medians of 20 launches in this run"}
 
 
 SETTLE = 60                        # untimed launches before the timed region, at least (see main)
@@ -235,6 +235,7 @@ def main():
 
     import torch
     import paper_2509_07003_amd as v
+    from paper_2509_07003_amd import bench_binding as B
     from paper_2509_07003_amd import workloads as W
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -300,7 +301,7 @@ def main():
     props = torch.cuda.get_device_properties(0)
     dev = {"name": props.name, "compute_units": props.multi_processor_count,
            "hbm_gib": round(props.total_memory / 2 ** 30, 1)}
-    cus, sclk_khz, mem_khz, bus_bits = v.vesrng_device_info()
+    cus, sclk_khz, mem_khz, bus_bits, wall_khz = B.vesrng_bench_device_info()
     # HBM3E at 8 Gb/s per pin makes four transfers per reported memory clock (2 GHz on MI355X).
     dev.update({"shader_clock_mhz": sclk_khz / 1e3, "memory_clock_mhz": mem_khz / 1e3, "memory_bus_bits": bus_bits,
                 "hbm_peak_at_4_transfers_per_clock_gb_per_s": 4 * mem_khz * 1e3 * bus_bits / 8 / 1e9,
@@ -317,7 +318,7 @@ def main():
 
     if not a.no_extra:
         del x, y, mask
-        ceil = measured_ceilings(v, torch)
+        ceil = measured_ceilings(B, torch)
         out["ceilings"] = ceil
         roofline["frac_of_measured_traffic_ceiling"] = achieved / ceil["dropout_traffic_gb_per_s"]
         roofline["frac_of_measured_generator_ceiling"] = (n / 4 / (avg_ms * 1e-3) / 1e9) / ceil["philox_only_gblocks_per_s"]

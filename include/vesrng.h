@@ -127,7 +127,10 @@ VESRNG_API vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n
 VESRNG_API vesrng_status vesrng_global_index_general(const vesrng_sharding* s, int64_t n,
                                                      const int64_t* local_index, uint64_t* global_index);
 
-/* Raw 32-bit draws: out[i] = word (p % 4) of block (p / 4), p = offset + j(i).  Test hook. */
+/* Raw 32-bit draws, Algorithm 1 with nothing after the generator call: "r <- lambda(alpha,
+ * tau_virtual, beta_virtual); chi_i <- r".  out[i] = word (p % 4) of block (p / 4), p = offset + j(i)
+ * (or the virtual-thread form when virtual_threads > 0); uint32, local_numel entries.  What the
+ * other operators convert; also how a test sees the index map and the generator on their own. */
 VESRNG_API vesrng_status vesrng_raw_u32(const vesrng_sharding* s, uint64_t seed, uint64_t offset,
                              uint32_t* out, void* hip_stream);
 
@@ -172,28 +175,8 @@ VESRNG_API vesrng_status vesrng_dropout_add(const vesrng_sharding* s, vesrng_dty
 VESRNG_API vesrng_status vesrng_randint(const vesrng_sharding* s, int64_t low, int64_t high, uint64_t seed,
                              uint64_t offset, int64_t* out, void* hip_stream);
 
-/* Measurement aid, not part of the method: plain kernels whose rates bound the real ones.
- * `units` 16-byte units are touched (STORE: written to out; COPY: in -> out; DROPOUT_TRAFFIC:
- * 16 bytes in, 16 bytes to out and 8 bytes to out2 per unit, the bf16 dropout kernel's accesses
- * without its arithmetic), or `units` Philox4x32-10 blocks are generated and discarded (PHILOX;
- * out must still be a valid device pointer of at least 1 KiB).  Device pointers, 16-byte aligned;
- * asynchronous on hip_stream. */
-typedef enum {
-  VESRNG_PROBE_STORE = 0,
-  VESRNG_PROBE_COPY = 1,
-  VESRNG_PROBE_DROPOUT_TRAFFIC = 2,
-  VESRNG_PROBE_PHILOX = 3
-} vesrng_probe_kind;
-VESRNG_API vesrng_status vesrng_probe(vesrng_probe_kind kind, uint64_t units, const void* in, void* out,
-                                      void* out2, void* hip_stream);
-
-/* Measurement aid: what the HIP runtime reports for the current device, for the roofline's
- * denominators.  Host pointers; any may be NULL.  On MI355X the runtime reports a memory clock
- * of 2,000,000 kHz and a bus of 8192 bits: HBM3E's 8 Gb/s per pin is four transfers per reported
- * clock, i.e. 4 * clock * bus / 8 = 8.19 TB/s, the published 8 TB/s. */
-VESRNG_API vesrng_status vesrng_device_info(int32_t* compute_units, int32_t* shader_clock_khz,
-                                            int32_t* memory_clock_khz, int32_t* memory_bus_bits);
-
+/* Text for a status code (a static string, never NULL): the error behaviour stated at the top of
+ * this header - every entry point reports through vesrng_status - made printable. */
 VESRNG_API const char* vesrng_status_string(vesrng_status st);
 
 #ifdef __cplusplus

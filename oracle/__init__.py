@@ -39,9 +39,7 @@ class _Flat(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
-            _build.build()
-        L = C.CDLL(_build.LIB)
+        L = C.CDLL(_build.ensure())   # rebuilt first when missing or older than its sources
         L.oracle_draw.restype = C.c_uint32
         L.oracle_draw.argtypes = [C.c_uint64, C.c_uint64]
         L.oracle_uniform_f32.restype = C.c_float

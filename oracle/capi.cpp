@@ -19,6 +19,12 @@ using namespace oracle;
 
 namespace {
 
+// Identity of the sources this library was built from (passed by oracle/build.py); the Python
+// front end finds it by scanning the file and rebuilds a stale library.
+#ifdef ORACLE_BUILD_ID
+__attribute__((used)) const char kOracleBuildId[] = "ORACLE_BUILD_ID=" ORACLE_BUILD_ID;
+#endif
+
 struct FlatSharding {
   int32_t ndim;
   const int64_t* global_shape;

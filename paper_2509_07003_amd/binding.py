@@ -26,16 +26,24 @@ class _Sharding(C.Structure):
 
 
 def library_path():
-    return _build.LIB
+    return _build.lib_path("vesrng")
 
 
-def _load():
-    if not os.path.exists(_build.LIB):
-        _build.build()
-    lib = C.CDLL(_build.LIB)
+class VesrngError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__("vesrng status %d: %s" % (status, vesrng_status_string(status)))
+
+
+def _check(status):
+    if status != 0:
+        raise VesrngError(status)
+
+
+def _signatures():
     st, vp, u64, i64, dbl, i32 = C.c_int, C.c_void_p, C.c_uint64, C.c_int64, C.c_double, C.c_int32
     sp = C.POINTER(_Sharding)
-    sigs = {
+    return {
         "vesrng_local_shape": [sp, C.POINTER(i64), C.POINTER(i64)],
         "vesrng_advance_offset": [sp, u64, C.POINTER(u64)],
         "vesrng_global_index": [sp, i64, C.POINTER(i64), C.POINTER(u64)],
@@ -46,25 +54,27 @@ def _load():
         "vesrng_dropout": [sp, i32, dbl, u64, u64, vp, vp, vp, vp],
         "vesrng_dropout_add": [sp, i32, dbl, u64, u64, vp, vp, vp, vp, vp],
         "vesrng_randint": [sp, i64, i64, u64, u64, vp, vp],
-        "vesrng_probe": [i32, u64, vp, vp, vp, vp],
-        "vesrng_device_info": [C.POINTER(i32)] * 4,
     }
-    for name, args in sigs.items():
+
+
+EXPORTS = sorted(list(_signatures()) + ["vesrng_status_string"])
+
+
+def load_library(path):
+    """ctypes handle of a library with the C ABI of include/vesrng.h, argument types declared."""
+    lib = C.CDLL(path)
+    for name, args in _signatures().items():
         fn = getattr(lib, name)
-        fn.restype = st
+        fn.restype = C.c_int
         fn.argtypes = args
     lib.vesrng_status_string.restype = C.c_char_p
-    lib.vesrng_status_string.argtypes = [st]
+    lib.vesrng_status_string.argtypes = [C.c_int]
     return lib
 
 
-_lib = _load()
-
-
-class VesrngError(RuntimeError):
-    def __init__(self, status):
-        self.status = status
-        super().__init__("vesrng status %d: %s" % (status, vesrng_status_string(status)))
+# Missing, or built from other sources than the ones present: rebuilt here; if that fails the
+# import fails.  There is nothing to fall back to.
+_lib = load_library(_build.ensure("vesrng"))
 
 
 def vesrng_status_string(status):
@@ -99,11 +109,6 @@ class Sharding:
     def with_coord(self, mesh_coord):
         return Sharding(self.global_shape, self.mesh_shape, self.placements, mesh_coord, self.global_stride,
                         self.virtual_threads)
-
-
-def _check(status):
-    if status != 0:
-        raise VesrngError(status)
 
 
 def _dev(buf):
@@ -186,20 +191,6 @@ def vesrng_dropout(sharding, dtype, p, seed, offset, x, y, mask=None, stream=Non
 def vesrng_dropout_add(sharding, dtype, p, seed, offset, x, residual, y, mask=None, stream=None):
     _check(_lib.vesrng_dropout_add(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(residual), _dev(y),
                                    _dev(mask), _stream(stream, x, residual, y, mask)))
-
-
-PROBE_STORE, PROBE_COPY, PROBE_DROPOUT_TRAFFIC, PROBE_PHILOX = 0, 1, 2, 3
-
-
-def vesrng_probe(kind, units, src, out, out2=None, stream=None):
-    _check(_lib.vesrng_probe(kind, units, _dev(src), _dev(out), _dev(out2), _stream(stream, src, out, out2)))
-
-
-def vesrng_device_info():
-    """(compute units, shader clock kHz, memory clock kHz, memory bus width in bits) of the current device."""
-    vals = [C.c_int32() for _ in range(4)]
-    _check(_lib.vesrng_device_info(*[C.byref(x) for x in vals]))
-    return tuple(x.value for x in vals)
 
 
 def vesrng_randint(sharding, low, high, seed, offset, out, stream=None):

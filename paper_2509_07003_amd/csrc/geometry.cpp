@@ -275,6 +275,47 @@ bool fits_32bit(const RunShape& rs, uint64_t units_per_run) {
   return true;
 }
 
+// A tile of T elements cut by B run boundaries touches at most T/4 + 1.5 (B + 1) blocks, plus one
+// dead slot per boundary when runs differ in phase; they must fit `passes` rounds of the workgroup.
+uint64_t pick_tile_units(uint64_t run_len, uint64_t unit_elems, uint64_t per_thread, bool phases_equal) {
+  const uint64_t passes = unit_elems / 4 * per_thread;
+  for (uint64_t q = kThreadsPerGroup * per_thread; q >= 32; q -= 8) {
+    const uint64_t t = q * unit_elems;
+    const uint64_t b = (t + run_len - 1) / run_len;
+    const uint64_t blocks = t / 4 + (3 * (b + 1) + 1) / 2 + (phases_equal ? 0 : b) + 1;
+    if (blocks <= passes * kThreadsPerGroup) return q;
+  }
+  return 0;
+}
+
+LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offset, const LaunchTraits& traits) {
+  const uint64_t V = traits.unit_elems;
+  const uint64_t pos0 = offset + g.origin;
+  LaunchChoice c;
+  // Aligned: every run starts on a block boundary and is whole units long - or the shard is a
+  // single run, whose last unit the aligned kernel finishes element by element (not randint,
+  // whose lanes trade halves of whole blocks).
+  if (rs.phases_equal && (pos0 % 4 == 0) &&
+      (rs.run_len % V == 0 || (rs.n_runs == 1 && !traits.whole_blocks_only))) {
+    c.flavour = kAligned;
+  } else if (rs.run_len >= 16) {
+    if (traits.big_tileable && static_cast<uint64_t>(g.local_numel) >= traits.big_tile_min_elems) {
+      c.tile_units = pick_tile_units(rs.run_len, V, kBigTileUnits, rs.phases_equal);
+      if (c.tile_units != 0) c.flavour = kTiledBig;
+    }
+    if (c.flavour == kRagged && traits.tileable) {
+      c.tile_units = pick_tile_units(rs.run_len, V, 1, rs.phases_equal);
+      if (c.tile_units != 0) c.flavour = kTiled;
+    }
+  }
+  // Aligned: units of V elements.  Otherwise: one unit per generator block a run can touch;
+  // with unequal phases the count is the upper bound over phases 0..3.
+  const uint64_t phase_max = rs.phases_equal ? (pos0 % 4) : 3;
+  c.units_per_run = c.flavour == kAligned ? (rs.run_len + V - 1) / V : (phase_max + rs.run_len + 3) / 4;
+  c.wide = !fits_32bit(rs, c.units_per_run);
+  return c;
+}
+
 template <typename IT>
 PlanT<IT> make_plan(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run) {
   PlanT<IT> p{};

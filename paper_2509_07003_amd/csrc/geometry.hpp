@@ -79,4 +79,33 @@ PlanT<IT> make_plan(const Geometry& g, const RunShape& rs, uint64_t offset, uint
 // True when every quantity of the plan fits the 32-bit index path.
 bool fits_32bit(const RunShape& rs, uint64_t units_per_run);
 
+// ---- which kernel a boxed shard takes ------------------------------------------
+// kAligned: every run starts on a generator-block boundary and is whole units long (or the
+// shard is a single run).  kTiled / kTiledBig: ragged shard staged through LDS, one or
+// kBigTileUnits aligned units per thread.  kRagged: one global block per thread, stored
+// in place.
+enum Flavour { kAligned, kTiled, kTiledBig, kRagged };
+constexpr int kThreadsPerGroup = 256;
+constexpr int kBigTileUnits = 4;
+
+// What the operator / dtype instantiation of the kernels can use.
+struct LaunchTraits {
+  uint64_t unit_elems = 4;          // elements per aligned unit (4, or 8 for the 16-bit floating-point operators)
+  bool tileable = false;            // has a staging kernel
+  bool big_tileable = false;        // ... and its large-tile form
+  uint64_t big_tile_min_elems = 0;  // smallest shard that takes the large tile
+  bool whole_blocks_only = false;   // the aligned kernel cannot finish a partial last unit (randint)
+};
+struct LaunchChoice {
+  Flavour flavour = kRagged;
+  uint64_t units_per_run = 0;  // aligned: units of unit_elems; otherwise generator blocks a run can touch
+  uint64_t tile_units = 0;     // staging kernels: aligned units per tile
+  bool wide = false;           // 64-bit index instantiation
+};
+LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offset, const LaunchTraits& traits);
+
+// Largest tile (in units, a multiple of 8 so that tiles start on 128-byte lines) whose
+// generator blocks fit the workgroup's passes; 0 = runs too short for tiling.
+uint64_t pick_tile_units(uint64_t run_len, uint64_t unit_elems, uint64_t per_thread, bool phases_equal);
+
 }  // namespace vesrng

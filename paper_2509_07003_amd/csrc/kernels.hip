@@ -38,9 +38,22 @@
 #include "plan.h"
 #include "stream_store.h"
 
+// 1 (always, in the library): keep the argument fetch in one batch - no early exit, operator
+// parameters live at kernel entry, the generator pinned above the bounds branch.  0 only in the
+// measurement variant that times the kernels without it.
+#ifndef VESRNG_PIN_ARGUMENT_FETCH
+#define VESRNG_PIN_ARGUMENT_FETCH 1
+#endif
+
 namespace vesrng {
 
 namespace {
+// The measurement variants of this file (one design choice flipped, built into libraries of their
+// own for the benchmark) put everything into a named namespace, so that their kernels appear
+// under their own names in a profiler's trace.  The library itself defines no tag.
+#ifdef VESRNG_VARIANT_TAG
+inline namespace VESRNG_VARIANT_TAG {
+#endif
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -54,19 +67,8 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
 typedef u32x2 u32x2_align4 __attribute__((aligned(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = kThreadsPerGroup;
 constexpr int kF32 = 0, kBF16 = 1, kF16 = 2;
-
-template <typename IT>
-struct SignedOf;
-template <>
-struct SignedOf<uint32_t> {
-  using type = int32_t;
-};
-template <>
-struct SignedOf<uint64_t> {
-  using type = int64_t;
-};
 
 // ---- conversions ---------------------------------------------------------------
 // Two fp32 values rounded (nearest even) to a pair of 16-bit floats of dtype DT, low half first,
@@ -291,6 +293,10 @@ __device__ __forceinline__ void emit_element(uint32_t v, const OpParams& prm, co
 // generator (the compiler otherwise loads them where the conversion first needs them).
 template <int OP>
 __device__ __forceinline__ void touch_params(const OpParams& prm) {
+#if !VESRNG_PIN_ARGUMENT_FETCH
+  (void)prm;
+  return;
+#endif
   if constexpr (OP == kOpUniform)
     asm volatile("" ::"s"(prm.width), "s"(prm.low), "s"(prm.cap), "s"(prm.unit_range));
   else if constexpr (OP == kOpNormal)
@@ -302,30 +308,7 @@ __device__ __forceinline__ void touch_params(const OpParams& prm) {
 }
 
 // ---- locating work ---------------------------------------------------------------
-// Stream position of the first element of run `run`.  NOUT is the number of
-// run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
-// shards (a contiguous slice; one strided axis of runs) need no loop and no argument
-// loads that depend on a loop counter.
-template <int NOUT, typename IT>
-__device__ __forceinline__ uint64_t run_position(const PlanT<IT>& plan, IT run) {
-  if constexpr (NOUT == 0) return plan.pos0;
-  else if constexpr (NOUT == 1) return plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
-  else return plan.pos0 + run_offset(plan, run);
-}
-
-// Work unit w -> (run, unit inside the run, stream position of the run).
-template <int NOUT, typename IT>
-__device__ __forceinline__ void locate(const PlanT<IT>& plan, IT w, IT& run, IT& unit, uint64_t& run_pos) {
-  if constexpr (NOUT == 0) {
-    run = 0;
-    unit = w;
-  } else {
-    run = plan.units_div.div(w);
-    unit = w - run * plan.units_per_run;
-  }
-  run_pos = run_position<NOUT>(plan, run);
-}
-
+// (run_position, locate and the tile map live in plan.h: the host evaluates them too.)
 // The part of global block `bi` of a run that belongs to the run.
 template <typename IT>
 struct BlockSpan {
@@ -357,7 +340,9 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   // Threads past the end compute unit 0 again and skip the stores: no early exit, so all
   // kernel arguments are fetched in one batch at the top.
   touch_params<OP>(prm);
+#if VESRNG_PIN_ARGUMENT_FETCH
   asm volatile("" ::"s"(out), "s"(mask));
+#endif
   uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   // randint writes 32 bytes per generator block.  Lane by lane that would be two stores of 16
   // bytes at a 32-byte stride, which run at a third of the contiguous rate.  Instead the lane
@@ -367,6 +352,10 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   const uint64_t wave_base = t64 - lane;
   if constexpr (OP == kOpRandint) t64 = wave_base + (lane >> 1) + ((lane & 1u) << 5);
   const bool live = t64 < plan.total_units;
+#if !VESRNG_PIN_ARGUMENT_FETCH
+  if constexpr (OP != kOpRandint)
+    if (!live) return;  // measurement variant: the plain early exit
+#endif
   const uint64_t w64 = live ? t64 : 0;
   const IT w = static_cast<IT>(w64);
   IT run, unit;
@@ -397,10 +386,12 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
   // Keep the generator (and the argument loads it needs) ahead of the bounds branch: without
   // this the compiler sinks everything below the branch and fetches the arguments in two
   // dependent rounds.
+#if VESRNG_PIN_ARGUMENT_FETCH
 #pragma unroll
   for (int b = 0; b < NB; ++b) asm volatile("" : "+v"(d[b][0]), "+v"(d[b][1]), "+v"(d[b][2]), "+v"(d[b][3]));
   if constexpr (kIsDropout<OP>) asm volatile("" : "+v"(xv));
   if constexpr (OP == kOpDropoutAdd) asm volatile("" : "+v"(rv));
+#endif
   if constexpr (OP == kOpRandint) {
     // All 64 lanes are still active here.  The even lane holds block k, the odd lane block
     // 32 + k; each hands the half its partner stores to the neighbouring lane (quad_perm
@@ -438,23 +429,12 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 }
 
 // ---- tiled kernels ---------------------------------------------------------------
-// plan.units_per_run counts the generator blocks a run can touch (as for the ragged
-// kernel).  `tile_units` aligned units of the local tensor form one workgroup's tile;
-// run_len_div divides by the run length.
-template <typename IT>
-struct TileArgs {
-  typename PlanT<IT>::Div run_len_div;
-  IT tile_units;
-  uint64_t local_numel;
-};
-
 // UPT: aligned units a thread takes out of the tile in stage B (the tile is up to kThreads * UPT
 // units).
 template <int OP, int DT, typename IT, int NOUT, int UPT>
 __global__ void __launch_bounds__(kThreads)
 tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, const void* xin, void* out,
              uint8_t* mask) {
-  using ST = typename SignedOf<IT>::type;
   constexpr int V = UnitOf<OP, DT>::kElems;
   // One 32-bit value per local element of the tile, plus a slot that swallows the lanes of
   // edge blocks that fall outside the tile or the run (cheaper than predicated LDS writes).
@@ -467,33 +447,19 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
   const int32_t lim = static_cast<int32_t>(i1 - i0);
 
   // Generator blocks that intersect [i0, i1): flattened (run, block) numbers wa .. wa + count - 1.
-  auto block_of = [&](uint64_t i) -> IT {
-    const IT ii = static_cast<IT>(i);
-    const IT run = ta.run_len_div.div(ii);
-    const IT c = ii - run * plan.run_len;
-    const uint32_t phase = static_cast<uint32_t>(run_position<NOUT>(plan, run)) & 3u;
-    return run * plan.units_per_run + ((c + phase) >> 2);
-  };
-  const IT wa = block_of(i0);
-  const IT count = block_of(i1 - 1) - wa + 1;
+  const IT wa = tile_block_of<NOUT>(plan, ta, i0);
+  const IT count = tile_block_of<NOUT>(plan, ta, i1 - 1) - wa + 1;
 
   // Stage A: one block per thread (one pass for 4-byte units, two for bfloat16 units).
-  // Everything is kept in tile coordinates (local index minus i0), which fit 32 bits.
   for (IT k = threadIdx.x; k < count; k += kThreads) {
-    IT run, bi;
-    uint64_t run_pos;
-    locate<NOUT>(plan, static_cast<IT>(wa + k), run, bi, run_pos);
+    const TileSpot spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
     uint32_t d[4], v[4];
-    philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
+    philox_block(spot.block, prm.key0, prm.key1, d);
     convert_block<OP, DT>(d, prm, v);
-    // The run occupies tile positions [run_lo, run_lo + run_len); lane e of this block sits at
-    // rel + e.  A lane is written when it is inside both the run and the tile; the other lanes
-    // of edge blocks (and the dead slots of runs that differ in phase) go to the dummy slot.
-    const int32_t run_lo = static_cast<int32_t>(static_cast<ST>(run * plan.run_len) - static_cast<ST>(i0));
-    const int32_t rel =
-        run_lo + static_cast<int32_t>(4 * bi) - static_cast<int32_t>(static_cast<uint32_t>(run_pos) & 3u);
-    const int32_t lo = max(run_lo, 0);
-    const int32_t hi = min(run_lo + static_cast<int32_t>(plan.run_len), lim);
+    // Word e of this block sits at tile position rel + e.  A word is written when it is inside
+    // both the run and the tile; the other words of edge blocks (and the dead slots of runs that
+    // differ in phase) go to the dummy slot.
+    const int32_t rel = spot.rel, lo = spot.lo, hi = spot.hi;
     if (rel >= lo && rel + 4 <= hi) {
       // Interior block (nearly all of them): four writes off one address.
 #pragma unroll
@@ -560,7 +526,9 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
 
   uint32_t d[4];
   philox_block((run_pos >> 2) + bi, prm.key0, prm.key1, d);
+#if VESRNG_PIN_ARGUMENT_FETCH
   asm volatile("" : "+v"(d[0]), "+v"(d[1]), "+v"(d[2]), "+v"(d[3]));  // see aligned_kernel
+#endif
   if (!in_range || !s.any) return;
 
   uint32_t v[4];
@@ -675,7 +643,8 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 }
 
 // ---- dispatch --------------------------------------------------------------------
-enum Flavour { kAligned, kTiled, kTiledBig, kRagged };
+// Which kernel a shard takes is decided on the host by choose_launch (geometry.cpp); the traits
+// below say what each operator can use.
 // Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
 // through LDS doubles the rate of bf16 dropout (5.8 vs 2.4 TB/s) and helps the raw fill
 // (5.4 vs 4.3), the fp32 uniform fill (5.1 vs 4.2) and randint.  The 16-bit fills lose (3.0 vs
@@ -692,9 +661,13 @@ constexpr bool kTileable =
 template <int OP, int DT>
 constexpr bool kBigTileable = ((OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) && UnitOf<OP, DT>::kElems == 4);
 // Smallest shard that takes the big tile (measured crossover: 2^24 elements, 2^26 for the normal fill).
+#ifdef VESRNG_BIG_TILE_MIN_ELEMS  // measurement variants only: force one tile size
+template <int OP>
+constexpr uint64_t kBigTileMinElems = VESRNG_BIG_TILE_MIN_ELEMS;
+#else
 template <int OP>
 constexpr uint64_t kBigTileMinElems = (OP == kOpNormal) ? (1ull << 26) : (1ull << 24);
-constexpr int kBigTileUnits = 4;
+#endif
 
 template <int OP, int DT, typename IT, int NOUT>
 hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
@@ -742,52 +715,21 @@ hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, 
   }
 }
 
-// Largest tile (in units, a multiple of 8 so that tiles start on 128-byte lines) whose
-// generator blocks fit `passes` rounds of the workgroup: a tile of T elements cut by B run
-// boundaries touches at most T/4 + 1.5 (B + 1) blocks, plus one dead slot per boundary when
-// runs differ in phase.  0 = runs too short for tiling.
-uint64_t pick_tile_units(uint64_t run_len, uint64_t V, uint64_t per_thread, bool phases_equal) {
-  const uint64_t passes = V / 4 * per_thread;
-  for (uint64_t q = kThreads * per_thread; q >= 32; q -= 8) {
-    const uint64_t t = q * V;
-    const uint64_t b = (t + run_len - 1) / run_len;
-    const uint64_t blocks = t / 4 + (3 * (b + 1) + 1) / 2 + (phases_equal ? 0 : b) + 1;
-    if (blocks <= passes * kThreads) return q;
-  }
-  return 0;
-}
-
 template <int OP, int DT>
 hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                      uint8_t* mask, hipStream_t stream) {
   if (!g.boxed || g.virtual_threads != 0) return launch_chain<OP, DT>(g, offset, prm, x, out, mask, stream);
   const RunShape rs = run_shape(g);
-  constexpr uint64_t V = UnitOf<OP, DT>::kElems;
-  const uint64_t pos0 = offset + g.origin;
-  Flavour flavour = kRagged;
-  uint64_t tile_units = 0;
-  // Aligned: every run starts on a block boundary and is whole units long - or the shard is a
-  // single run, whose last unit the aligned kernel finishes element by element (not randint,
-  // whose lanes trade halves of whole blocks).
-  if (rs.phases_equal && (pos0 % 4 == 0) && (rs.run_len % V == 0 || (rs.n_runs == 1 && OP != kOpRandint))) {
-    flavour = kAligned;
-  } else if (rs.run_len >= 16) {
-    if (kBigTileable<OP, DT> && static_cast<uint64_t>(g.local_numel) >= kBigTileMinElems<OP>) {
-      tile_units = pick_tile_units(rs.run_len, V, kBigTileUnits, rs.phases_equal);
-      if (tile_units != 0) flavour = kTiledBig;
-    }
-    if (flavour == kRagged && kTileable<OP, DT>) {
-      tile_units = pick_tile_units(rs.run_len, V, 1, rs.phases_equal);
-      if (tile_units != 0) flavour = kTiled;
-    }
-  }
-  // Aligned: units of V elements.  Otherwise: one unit per generator block a run can touch;
-  // with unequal phases the count is the upper bound over phases 0..3.
-  const uint64_t phase_max = rs.phases_equal ? (pos0 % 4) : 3;
-  const uint64_t units = flavour == kAligned ? (rs.run_len + V - 1) / V : (phase_max + rs.run_len + 3) / 4;
-  if (fits_32bit(rs, units))
-    return launch_typed<OP, DT, uint32_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
-  return launch_typed<OP, DT, uint64_t>(flavour, g, rs, offset, units, tile_units, prm, x, out, mask, stream);
+  LaunchTraits traits;
+  traits.unit_elems = UnitOf<OP, DT>::kElems;
+  traits.tileable = kTileable<OP, DT>;
+  traits.big_tileable = kBigTileable<OP, DT>;
+  traits.big_tile_min_elems = kBigTileMinElems<OP>;
+  traits.whole_blocks_only = (OP == kOpRandint);
+  const LaunchChoice c = choose_launch(g, rs, offset, traits);
+  if (c.wide)
+    return launch_typed<OP, DT, uint64_t>(c.flavour, g, rs, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
+  return launch_typed<OP, DT, uint32_t>(c.flavour, g, rs, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
 }
 
 // The floating-point operators, by output dtype.
@@ -802,6 +744,9 @@ hipError_t launch_float(const Geometry& g, uint64_t offset, const OpParams& prm,
   return hipErrorInvalidValue;
 }
 
+#ifdef VESRNG_VARIANT_TAG
+}  // inline namespace
+#endif
 }  // namespace
 
 hipError_t launch_op(OpKind op, const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,

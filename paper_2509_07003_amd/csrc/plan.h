@@ -83,7 +83,9 @@ struct PlanT {
 template <typename IT>
 VESRNG_HD uint64_t run_offset(const PlanT<IT>& p, IT o) {
   uint64_t off = 0;
+#if defined(__HIPCC__)
 #pragma unroll 1
+#endif
   for (int k = 0; k + 1 < p.n_outer; ++k) {
     const IT q = p.outer_div[k].div(o);
     const IT c = o - q * p.outer_extent[k];
@@ -92,6 +94,88 @@ VESRNG_HD uint64_t run_offset(const PlanT<IT>& p, IT o) {
   }
   if (p.n_outer > 0) off += static_cast<uint64_t>(o) * p.outer_stride[p.n_outer - 1];
   return off;
+}
+
+template <typename IT>
+struct SignedOf;
+template <>
+struct SignedOf<uint32_t> {
+  using type = int32_t;
+};
+template <>
+struct SignedOf<uint64_t> {
+  using type = int64_t;
+};
+
+// Stream position of the first element of run `run`.  NOUT is the number of
+// run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
+// shards (a contiguous slice; one strided axis of runs) need no loop and no argument
+// loads that depend on a loop counter.
+template <int NOUT, typename IT>
+VESRNG_HD uint64_t run_position(const PlanT<IT>& plan, IT run) {
+  if constexpr (NOUT == 0) return plan.pos0;
+  else if constexpr (NOUT == 1) return plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
+  else return plan.pos0 + run_offset(plan, run);
+}
+
+// Work unit w -> (run, unit inside the run, stream position of the run).
+template <int NOUT, typename IT>
+VESRNG_HD void locate(const PlanT<IT>& plan, IT w, IT& run, IT& unit, uint64_t& run_pos) {
+  if constexpr (NOUT == 0) {
+    run = 0;
+    unit = w;
+  } else {
+    run = plan.units_div.div(w);
+    unit = w - run * plan.units_per_run;
+  }
+  run_pos = run_position<NOUT>(plan, run);
+}
+
+// ---- tile map of the staging kernel ---------------------------------------------
+// A workgroup of the staging kernel owns a tile of the LOCAL tensor (elements [i0, i0 + lim))
+// and first computes the GLOBAL generator blocks that intersect it.  plan.units_per_run counts
+// the blocks a run can touch; a block is named by its flattened number run * units_per_run + bi.
+template <typename IT>
+struct TileArgs {
+  typename PlanT<IT>::Div run_len_div;  // divides by the run length
+  IT tile_units;                        // aligned units of the local tensor per tile
+  uint64_t local_numel;
+};
+
+// Flattened number of the generator block that holds local element i.
+template <int NOUT, typename IT>
+VESRNG_HD IT tile_block_of(const PlanT<IT>& plan, const TileArgs<IT>& ta, uint64_t i) {
+  const IT ii = static_cast<IT>(i);
+  const IT run = ta.run_len_div.div(ii);
+  const IT c = ii - run * plan.run_len;
+  const uint32_t phase = static_cast<uint32_t>(run_position<NOUT>(plan, run)) & 3u;
+  return run * plan.units_per_run + ((c + phase) >> 2);
+}
+
+// Where generator block w lands in the tile, in tile coordinates (local index minus i0): word e of
+// the block sits at rel + e, and is written when lo <= rel + e < hi, the part of the block's run
+// that lies inside the tile.  The run itself may start far before the tile and end far after it
+// (a run of 2^32 elements and more is possible), so its bounds are clamped to the tile in the index
+// type BEFORE they are narrowed; rel lies within a block of the tile by construction.
+struct TileSpot {
+  uint64_t block;   // generator block number in the stream
+  int32_t rel, lo, hi;
+};
+template <int NOUT, typename IT>
+VESRNG_HD TileSpot tile_spot(const PlanT<IT>& plan, uint64_t i0, int32_t lim, IT w) {
+  using ST = typename SignedOf<IT>::type;
+  IT run, bi;
+  uint64_t run_pos;
+  locate<NOUT>(plan, w, run, bi, run_pos);
+  const ST run_lo = static_cast<ST>(run * plan.run_len) - static_cast<ST>(i0);
+  const ST run_hi = run_lo + static_cast<ST>(plan.run_len);
+  const ST zero = 0, top = static_cast<ST>(lim);
+  TileSpot s;
+  s.block = (run_pos >> 2) + bi;
+  s.rel = static_cast<int32_t>(run_lo + static_cast<ST>(4 * bi) - static_cast<ST>(static_cast<uint32_t>(run_pos) & 3u));
+  s.lo = static_cast<int32_t>(run_lo > zero ? (run_lo < top ? run_lo : top) : zero);
+  s.hi = static_cast<int32_t>(run_hi < top ? (run_hi > zero ? run_hi : zero) : top);
+  return s;
 }
 
 // ---- chain plan: the general index map ---------------------------------------

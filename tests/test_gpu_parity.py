@@ -412,6 +412,42 @@ def test_wide_index_path_beyond_2_to_31_local_elements():
     for b, e in ((0, 8192), (ln // 2 - 4096, ln // 2 + 4096), (ln - 8192, ln)):
         want = oracle.raw_u32(args, 22, 1 << 36, i_begin=b, i_end=e).reshape(-1)[b:e]
         assert np.array_equal(out[b:e].cpu().numpy().view(np.uint32), want), (b, e)
+    del out
+
+
+def test_single_misaligned_run_of_more_than_2_to_32_elements():
+    """One contiguous shard of 2^32 + 1 elements that starts off a generator-block boundary: the staging
+    kernel's large-tile form with a single run longer than any 32-bit quantity (its tile map is checked
+    slot by slot on the host by the sanitizer tests; here the kernel itself, on sampled windows, for the
+    raw draws, and the normal fill through the same path).  A 1-D tensor of 2^33 + 2 elements is never
+    listed by the oracle: the shard's values are those of the unsharded stream at offset + 2^32 + 1."""
+    run = (1 << 32) + 1
+    shape, mesh, pls, c = [2 * run], [2], [("S", 0)], [1]
+    sh = v.Sharding(shape, mesh, pls, c)
+    assert v.vesrng_local_shape(sh) == ([run], run)
+    seed, offset = 77, 1 << 40
+    windows = ((0, 6000), ((1 << 31) - 6000, (1 << 31) + 6000), ((1 << 32) - 6000, run))
+    out = torch.empty(run, dtype=torch.int32, device=DEV)
+    say("misaligned run: raw fill of %d elements" % run)
+    v.vesrng_raw_u32(sh, seed, offset, out)
+    torch.cuda.synchronize()
+    for b, e in windows:
+        # Offset additivity (a pinned property of the oracle): element i of the shard is element
+        # i - b of a small unsharded tensor whose stream starts 4-aligned just below offset + run + b.
+        p0 = offset + run + b
+        base = p0 - p0 % 4
+        flat = oracle.raw_u32(([e - b + 4], [1], [("R",)], [0]), seed, base)
+        assert np.array_equal(out[b:e].cpu().numpy().view(np.uint32), flat[p0 - base:p0 - base + e - b]), (b, e)
+    say("misaligned run: fp32 normal fill")
+    outf = out.view(torch.float32)
+    v.vesrng_normal(sh, v.F32, 0.0, 1.0, seed, offset, outf)
+    torch.cuda.synchronize()
+    for b, e in windows:
+        p0 = offset + run + b
+        base = p0 - p0 % 4
+        ref = oracle.normal_f64_values(([e - b + 4], [1], [("R",)], [0]), 0.0, 1.0, seed, base)[p0 - base:p0 - base + e - b]
+        err = np.abs(outf[b:e].cpu().numpy().astype(np.float64) - ref)
+        assert (err <= 1e-6 * np.maximum(np.abs(ref), 1.0)).all(), (b, e)
 
 
 # ------------------------------------------- general route and global stride ---
@@ -624,26 +660,54 @@ def test_random_descriptions_all_kernel_flavours():
 
 
 def test_ceiling_probes_do_what_they_say():
-    """The measurement aids: store pattern, copy, dropout traffic pattern, generator-only; and the
-    device properties the roofline's denominators come from."""
-    cus, shader_khz, memory_khz, bus_bits = v.vesrng_device_info()
+    """The measurement aids (their own library): store patterns in every form, copy, dropout traffic
+    pattern, generator-only and issue-rate loops, the clock probe and the device properties the
+    roofline's denominators come from."""
+    from paper_2509_07003_amd import bench_binding as b
+    cus, shader_khz, memory_khz, bus_bits, wall_khz = b.vesrng_bench_device_info()
     assert cus == torch.cuda.get_device_properties(0).multi_processor_count
-    assert shader_khz > 0 and memory_khz > 0 and bus_bits >= 1024
+    assert shader_khz > 0 and memory_khz > 0 and bus_bits >= 1024 and wall_khz > 0
     units = 4096 + 3
-    a = torch.zeros(units * 4, dtype=torch.int32, device=DEV)
-    v.vesrng_probe(v.PROBE_STORE, units, None, a)
+    want = np.arange(units, dtype=np.int32)[:, None] + np.arange(4, dtype=np.int32)[None, :]
+    for kind in (b.PROBE_STORE, b.PROBE_STORE_NT, b.PROBE_STORE_PLAIN, b.PROBE_STORE_GRID_STRIDE,
+                 b.PROBE_STORE_4_PER_THREAD):
+        say("store probe %d" % kind)
+        a = torch.zeros(units * 4 + 4, dtype=torch.int32, device=DEV)
+        b.vesrng_bench_probe(kind, units, None, a)
+        torch.cuda.synchronize()
+        got = a.cpu().numpy()
+        assert np.array_equal(got[:units * 4].reshape(units, 4), want), kind
+        assert not got[units * 4:].any(), kind                      # nothing past the last unit
+    # Unaligned form: unit t at words 4t + 1 .. 4t + 4, the last unit left out.
+    u = torch.zeros(units * 4, dtype=torch.int32, device=DEV)
+    b.vesrng_bench_probe(b.PROBE_STORE_UNALIGNED, units, None, u)
     torch.cuda.synchronize()
-    got = a.cpu().numpy().reshape(units, 4)
-    assert np.array_equal(got, np.arange(units, dtype=np.int32)[:, None] + np.arange(4, dtype=np.int32)[None, :])
-    b = torch.zeros_like(a)
-    v.vesrng_probe(v.PROBE_COPY, units, a, b)
-    m = torch.zeros(units * 2, dtype=torch.int32, device=DEV)
-    c = torch.zeros_like(a)
-    v.vesrng_probe(v.PROBE_DROPOUT_TRAFFIC, units, a, c, m)
-    v.vesrng_probe(v.PROBE_PHILOX, 1 << 20, None, b)     # generates and discards: b must stay a copy of a
+    got = u.cpu().numpy()
+    assert got[0] == 0 and np.array_equal(got[1:4 * (units - 1) + 1].reshape(units - 1, 4), want[:units - 1])
+    assert not got[4 * (units - 1) + 1:].any()
+    a = a[:units * 4].clone()
+    bb = torch.zeros_like(a)
+    b.vesrng_bench_probe(b.PROBE_COPY, units, a, bb)
+    for kind in (b.PROBE_DROPOUT_TRAFFIC, b.PROBE_DROPOUT_TRAFFIC_NT):
+        m = torch.zeros(units * 2, dtype=torch.int32, device=DEV)
+        c = torch.zeros_like(a)
+        b.vesrng_bench_probe(kind, units, a, c, m)
+        torch.cuda.synchronize()
+        assert torch.equal(a, c)
+        assert np.array_equal(m.cpu().numpy().reshape(units, 2), want[:, :2] & 0x01010101)
+    # Generator-only and issue-rate loops generate and discard: bb must stay a copy of a.
+    b.vesrng_bench_probe(b.PROBE_PHILOX, 1 << 20, None, bb)
+    b.vesrng_bench_probe(b.PROBE_PHILOX_TWO_XOR, 1 << 20, None, bb)
+    for cls in range(len(b.ALU_CLASSES)):
+        say("issue-rate loop %s" % b.ALU_CLASSES[cls])
+        b.vesrng_bench_alu(cls, 64, 4, bb)
     torch.cuda.synchronize()
-    assert torch.equal(a, b) and torch.equal(a, c)
-    assert np.array_equal(m.cpu().numpy().reshape(units, 2), got[:, :2] & 0x01010101)
+    assert torch.equal(a, bb)
+    ticks = torch.zeros(4, dtype=torch.int64, device=DEV)
+    b.vesrng_bench_clock(2000, ticks)
+    torch.cuda.synchronize()
+    t = ticks.cpu().numpy()
+    assert t[0] > 0 and t[1] > 0 and t[3] == 2000
 
 
 def test_in_place_dropout_on_ragged_and_non_box_shards():

@@ -12,19 +12,75 @@ import pytest
 import oracle
 import paper_2509_07003_amd as v
 from helpers import all_placements, mesh_coords
+from paper_2509_07003_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "vesrng.h")).read()
-    declared = sorted(set(re.findall(r"\b(vesrng_[a-z0-9_]+)\s*\(", header)))
-    assert {"vesrng_uniform", "vesrng_normal", "vesrng_dropout", "vesrng_advance_offset",
-            "vesrng_local_shape", "vesrng_raw_u32", "vesrng_randint", "vesrng_global_index",
-            "vesrng_status_string"} <= set(declared)
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
+    return sorted(set(re.findall(r"\b(vesrng_[a-z0-9_]+)\s*\(", header)))
+
+
+def _exported(path):
+    """Names in the dynamic symbol table of a shared library that it defines itself (hipcc's own
+    one-byte compilation-unit markers, __hip_cuid_<hash>, aside)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, stdout=subprocess.PIPE, text=True).stdout
+    names = [line.split()[-1] for line in out.splitlines() if line.split()[1] in "TDBRWV"]
+    return sorted(n for n in names if not n.startswith("__hip_cuid_"))
+
+
+def test_library_exports_exactly_the_declared_symbols():
+    """libvesrng.so exports the entry points include/vesrng.h declares - the method's operators, the
+    host-side geometry / offset calls and the two host test hooks - and nothing else: no measurement
+    aid, no stray C++ symbol."""
+    declared = _declared("vesrng.h")
+    assert declared == ["vesrng_advance_offset", "vesrng_dropout", "vesrng_dropout_add", "vesrng_global_index",
+                        "vesrng_global_index_general", "vesrng_local_shape", "vesrng_normal", "vesrng_randint",
+                        "vesrng_raw_u32", "vesrng_status_string", "vesrng_uniform"]
+    assert _exported(v.library_path()) == declared
+    assert declared == binding.EXPORTS
     lib = ctypes.CDLL(v.library_path())
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_bench_library_exports_exactly_its_header_and_is_separate():
+    """The measurement aids live in their own header and library, which the product binding never loads."""
+    from paper_2509_07003_amd import bench_binding
+    declared = _declared("vesrng_bench.h")
+    assert declared == bench_binding.EXPORTS
+    assert _exported(bench_binding.library_path()) == declared
+    assert bench_binding.library_path() != v.library_path()
+    src = open(os.path.join(ROOT, "paper_2509_07003_amd", "binding.py")).read()
+    assert "bench" not in src and "probe" not in src
+
+
+def test_loaders_rebuild_a_stale_library(tmp_path):
+    """A library built from other sources than the ones present is not loaded as it is: the build
+    identity embedded in the binary must match the hash of the sources, for the product and the oracle."""
+    from paper_2509_07003_amd import build as lib_build
+    from oracle import build as oracle_build
+    for t in lib_build.TARGETS:
+        assert lib_build.is_current(t), t
+    assert oracle_build.is_current()
+    assert lib_build.built_id("vesrng") == lib_build.source_id("vesrng") != lib_build.source_id("bench")
+    # The same check fails on a tree whose sources differ from the binary's (one byte appended).
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2509_07003_amd"
+    shutil.copytree(os.path.join(ROOT, "paper_2509_07003_amd"), pkg, ignore=shutil.ignore_patterns("__pycache__", "*variant*"))
+    shutil.copytree(os.path.join(ROOT, "include"), tmp_path / "include")
+    with open(pkg / "csrc" / "plan.h", "a") as f:
+        f.write("\n")
+    assert (pkg / "libvesrng.so").exists()
+    env = dict(os.environ, HIPCC="/bin/false", PYTHONPATH=str(tmp_path))
+    res = subprocess.run([sys.executable, "-c", "import paper_2509_07003_amd"], env=env, cwd=str(tmp_path),
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    # The binary is there, but stale: the loader tries to rebuild it and, unable to, refuses to load it.
+    assert res.returncode != 0 and "hipcc failed building libvesrng.so" in res.stderr
 
 
 def test_status_strings():
@@ -188,11 +244,15 @@ def test_error_paths_return_their_status_without_touching_the_gpu():
     assert _status(v.vesrng_randint, ok, 0, (1 << 32) + 1, 1, 0, buf) == 7
     assert _status(v.vesrng_raw_u32, ok, 1, 0, None) == 1
     assert _status(v.vesrng_raw_u32, v.Sharding([4], [2], [("P",)], [0]), 1, 0, buf) == 5
-    assert _status(v.vesrng_probe, v.PROBE_COPY, 16, None, buf) == 1
-    assert _status(v.vesrng_probe, v.PROBE_DROPOUT_TRAFFIC, 16, buf, buf, None) == 1
-    assert _status(v.vesrng_probe, v.PROBE_STORE, 16, None, buf + 8) == 12
-    assert _status(v.vesrng_probe, 9, 16, buf, buf, buf) == 7
-    v.vesrng_probe(v.PROBE_STORE, 0, None, None)
+    from paper_2509_07003_amd import bench_binding as b
+    assert _status(b.vesrng_bench_probe, b.PROBE_COPY, 16, None, buf) == 1
+    assert _status(b.vesrng_bench_probe, b.PROBE_DROPOUT_TRAFFIC, 16, buf, buf, None) == 1
+    assert _status(b.vesrng_bench_probe, b.PROBE_STORE, 16, None, buf + 8) == 12
+    assert _status(b.vesrng_bench_probe, 99, 16, buf, buf, buf) == 7
+    assert _status(b.vesrng_bench_alu, 99, 16, 16, buf) == 7
+    assert _status(b.vesrng_bench_alu, 0, 16, 16, None) == 1
+    assert _status(b.vesrng_bench_clock, 16, None) == 1
+    b.vesrng_bench_probe(b.PROBE_STORE, 0, None, None)
     # Empty shard: fine, nothing to launch, pointers not needed.
     v.vesrng_uniform(v.Sharding([3, 5], [4], [("S", 0)], [3]), v.F32, 0.0, 1.0, 1, 0, None)
     v.vesrng_dropout(v.Sharding([0]), v.BF16, 0.1, 1, 0, None, None, None)

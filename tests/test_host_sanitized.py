@@ -1,0 +1,251 @@
+"""The library's host code under AddressSanitizer and UndefinedBehaviorSanitizer (no GPU):
+tests/host_check.cpp is built with g++ -fsanitize=address,undefined from the library's own
+geometry.cpp and host_api.cpp and fed the brute-force grid of rank descriptions, random
+descriptions with strides, descriptions at and beyond the fixed capacities, and tile-map requests
+for shards too large to generate.  A sanitizer report aborts the program, which fails the test."""
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import all_placements, mesh_coords
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2509_07003_amd", "csrc")
+KIND = {"R": 0, "S": 1, "IS": 2, "P": 3}
+
+
+@pytest.fixture(scope="module")
+def host_check(tmp_path_factory):
+    exe = str(tmp_path_factory.mktemp("host_check") / "host_check")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-Wall", "-Wextra", os.path.join(ROOT, "tests", "host_check.cpp"), os.path.join(CSRC, "geometry.cpp"),
+           os.path.join(CSRC, "host_api.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True)
+
+    def run(lines):
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=1", UBSAN_OPTIONS="halt_on_error=1")
+        env.pop("LD_PRELOAD", None)   # the sanitizer runtime must come first in the program's library list
+        res = subprocess.run([exe], input="\n".join(lines) + "\n", stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                             text=True, env=env)
+        assert res.returncode == 0, "sanitizer report or crash:\n" + res.stderr[-4000:]
+        out = res.stdout.splitlines()
+        assert len(out) == len(lines)
+        return out
+
+    return run
+
+
+def sharding_words(shape, mesh, pls, coord, stride=None, theta=0):
+    w = [len(shape)] + list(shape) + ([1] + list(stride) if stride is not None else [0])
+    w += [len(mesh)] + list(mesh)
+    for p in pls:
+        w += [KIND[p[0]], p[1] if len(p) > 1 else 0, p[2] if len(p) > 2 else 1]
+    return " ".join(str(int(x)) for x in w + list(coord) + [theta])
+
+
+def parse_g(line):
+    t = line.split()
+    assert t[0] == "G"
+    status, nd = int(t[1]), int(t[2])
+    res = {"status": status}
+    k = 3
+    if status == 0:
+        res["shape"] = [int(x) for x in t[k:k + nd]]
+        res["numel"] = int(t[k + nd])
+        k += nd + 1
+        if t[k] == "J":
+            n = res["numel"]
+            res["J_status"], res["J"] = int(t[k + 1]), [int(x) for x in t[k + 2:k + 2 + n]]
+            k += 2 + n
+            assert t[k] == "K"
+            res["K_status"], res["K"] = int(t[k + 1]), [int(x) for x in t[k + 2:k + 2 + n]]
+            k += 2 + n
+    assert t[k] == "A"
+    res["A_status"], res["next"] = int(t[k + 1]), int(t[k + 2])
+    return res
+
+
+SHAPES = [[1], [7], [12], [2, 6], [6, 4], [5, 3], [3, 4, 2], [4, 6, 3], [2, 3, 2, 4], [1, 6, 1, 3]]
+MESHES = [[1], [2], [3], [4], [2, 2], [2, 3], [3, 2], [4, 2], [2, 2, 2]]
+
+
+def test_brute_force_grid_under_the_sanitizers(host_check):
+    """Every rank of every mesh / placement assignment of the grid: local shape, the i -> j map of the
+    kernels' decode plan and of the general route, and the offset advance, against the oracle."""
+    cases, lines = [], []
+    for shape in SHAPES:
+        for mesh in MESHES:
+            for pls in all_placements(len(shape), len(mesh)):
+                for c in mesh_coords(mesh):
+                    cases.append((shape, mesh, list(pls), list(c)))
+                    lines.append("G " + sharding_words(shape, mesh, pls, c) + " 100000")
+    out = host_check(lines)
+    checked = 0
+    for (shape, mesh, pls, c), line in zip(cases, out):
+        got = parse_g(line)
+        try:
+            want_shape, want_n = oracle.local_shape(shape, mesh, pls, c)
+        except oracle.OracleError:
+            assert got["status"] == 5, (shape, mesh, pls, c)
+            continue
+        assert got["status"] == 0 and got["shape"] == want_shape and got["numel"] == want_n, (shape, mesh, pls, c)
+        assert got["A_status"] == 0 and got["next"] == oracle.advance_offset(shape, 0)
+        if want_n:
+            want_j = [int(x) for x in oracle.global_indices(shape, mesh, pls, c).reshape(-1)]
+            assert got["J_status"] == 0 and got["J"] == want_j, (shape, mesh, pls, c)
+            assert got["K_status"] == 0 and got["K"] == want_j, (shape, mesh, pls, c)
+        checked += 1
+    assert checked > 29000
+
+
+def test_random_descriptions_with_strides_under_the_sanitizers(host_check):
+    from test_host_abi import _random_description
+    rng = np.random.default_rng(20240607)
+    cases = [_random_description(rng) for _ in range(1500)]
+    out = host_check(["G " + sharding_words(*c) + " 100000" for c in cases])
+    ok = 0
+    for (shape, mesh, pls, coord, stride), line in zip(cases, out):
+        got = parse_g(line)
+        try:
+            want_shape, want_n = oracle.local_shape(shape, mesh, pls, coord)
+        except oracle.OracleError:
+            assert got["status"] != 0
+            continue
+        assert got["status"] == 0 and got["shape"] == want_shape and got["numel"] == want_n
+        assert got["next"] == oracle.advance_offset(shape, 0, stride)
+        if want_n:
+            want_j = [int(x) for x in oracle.global_indices(shape, mesh, pls, coord, stride).reshape(-1)]
+            assert got["J"] == want_j and got["K"] == want_j, (shape, mesh, pls, coord, stride)
+        ok += 1
+    assert ok > 1000
+
+
+def test_descriptions_at_and_beyond_the_fixed_capacities(host_check):
+    """The geometry keeps its lists in fixed-size arrays (8 dimensions, 8 placements per dimension, 12
+    axes per dimension): what fits is answered, what does not is refused with a status - never an
+    overrun (the sanitizers watch)."""
+    lines, want = [], []
+
+    def add(words, status):
+        lines.append("G " + words + " 5000")
+        want.append(status)
+
+    # Eight placements on ONE dimension: the capacity.  All interleaved, so every one adds an axis.
+    shape = [2 ** 16]
+    for kinds in ([("IS", 0, 2)] * 8, [("S", 0)] * 8, [("IS", 0, 4), ("S", 0)] * 4, [("IS", 0, 2), ("IS", 0, 8)] * 4):
+        for coord in ([0] * 8, [1] * 8, [1, 0] * 4):
+            add(sharding_words(shape, [2] * 8, kinds, coord), None)
+    # Eight dimensions, every one interleaved by its own mesh dimension.
+    add(sharding_words([4] * 8, [2] * 8, [("IS", d, 2) for d in range(8)], [1] * 8), None)
+    # Beyond the capacities: refused by status.
+    add(sharding_words([2] * 9, [1], [("R",)], [0]), 2)                       # nine tensor dimensions
+    add(sharding_words([64], [2] * 9, [("S", 0)] * 9, [0] * 9), 3)            # nine mesh dimensions
+    add(sharding_words([64], [2], [("S", 3)], [0]), 5)                        # dimension out of range
+    add(sharding_words([64], [2], [("S", -1)], [0]), 5)
+    add(sharding_words([64], [2], [("IS", 0, 0)], [0]), 5)
+    add(sharding_words([64], [2], [("IS", 0, -4)], [0]), 5)
+    add(sharding_words([64], [2], [("S", 0)], [2]), 4)
+    add(sharding_words([64, -1], [2], [("S", 0)], [1]), 2)
+    add(sharding_words([2 ** 40, 2 ** 40], [1], [("R",)], [0]), 2)            # element count beyond 2^62
+    add(sharding_words([2 ** 31, 2 ** 30], [2], [("S", 0)], [1], stride=[2 ** 62, 1]), 10)   # stride overflow
+    add(sharding_words([4, 4], [1], [("R",)], [0], stride=[4, 0]), 10)
+    out = host_check(lines)
+    for line, st in zip(out, want):
+        got = parse_g(line)
+        if st is not None:
+            assert got["status"] == st, line[:80]
+            continue
+        assert got["status"] in (0, 9), line[:80]          # answered, or "unsupported": nothing in between
+        if got["status"] == 0 and "J" in got:
+            assert got["J"] == got["K"]                       # the two routes agree where both exist
+    # The capacity cases against the oracle (its lists have no capacity).
+    for kinds in ([("IS", 0, 2)] * 8, [("IS", 0, 4), ("S", 0)] * 4):
+        for coord in ([0] * 8, [1, 0] * 4):
+            got = parse_g(host_check(["G " + sharding_words(shape, [2] * 8, kinds, coord) + " 5000"])[0])
+            want_shape, want_n = oracle.local_shape(shape, [2] * 8, kinds, coord)
+            assert got["status"] == 0 and got["shape"] == want_shape
+            assert got["K"] == [int(x) for x in oracle.global_indices(shape, [2] * 8, kinds, coord).reshape(-1)]
+            assert got["J"] == got["K"]
+
+
+# ------------------------------------------------------------------ tile map ----
+def parse_t(line):
+    head, *tiles = line.split(" | ")
+    t = head.split()
+    assert t[0] == "T" and t[1] == "0", line[:200]
+    res = {"flavour": int(t[2]), "wide": int(t[3]), "units_per_run": int(t[4]), "tile_units": int(t[5]),
+           "n_tiles": int(t[6]), "tiles": []}
+    for tile in tiles:
+        w = tile.split()
+        assert w[0] != "OUT-OF-TILE", "the kernel would write outside its LDS tile: " + tile[:100]
+        i0, lim, count, dummy = int(w[0]), int(w[1]), int(w[2]), int(w[3])
+        res["tiles"].append({"i0": i0, "lim": lim, "count": count, "dummy": dummy, "pos": [int(x) for x in w[4:]]})
+    return res
+
+
+TILED, TILED_BIG = 1, 2
+
+
+def tile_request(words, offset, unit_elems, tileable, big, big_min, whole, tiles):
+    return "T %s %d %d %d %d %d %d %d %s" % (words, offset, unit_elems, tileable, big, big_min, whole, len(tiles),
+                                             " ".join(str(t) for t in tiles))
+
+
+def check_tiles(host_check, words, offset, unit_elems, big, position_of, local_numel, probe_elements, threads_units=256):
+    """Asks for the tiles that hold the given local elements (plus the first and last two) and checks
+    every slot: written exactly once, by the stream position of its local element."""
+    first = parse_t(host_check([tile_request(words, offset, unit_elems, 1, big, 0, 0, [])])[0])
+    assert first["flavour"] == (TILED_BIG if big else TILED)
+    per = first["tile_units"] * unit_elems
+    assert first["n_tiles"] == -(-local_numel // per)
+    assert 32 <= first["tile_units"] <= threads_units * (4 if big else 1) and first["tile_units"] % 8 == 0
+    want = sorted({0, 1, first["n_tiles"] - 2, first["n_tiles"] - 1} | {e // per for e in probe_elements}
+                  | {e // per + 1 for e in probe_elements} | {max(0, e // per - 1) for e in probe_elements})
+    want = [t for t in want if 0 <= t < first["n_tiles"]]
+    got = parse_t(host_check([tile_request(words, offset, unit_elems, 1, big, 0, 0, want)])[0])
+    assert len(got["tiles"]) == len(want)
+    passes = (unit_elems // 4) * (4 if big else 1)
+    for t, tile in zip(want, got["tiles"]):
+        assert tile["i0"] == t * per and tile["lim"] == min(per, local_numel - t * per)
+        assert tile["count"] <= passes * 256, "more generator blocks than the workgroup's passes cover"
+        i = np.arange(tile["i0"], tile["i0"] + tile["lim"], dtype=np.uint64)
+        assert tile["pos"] == [int(p) for p in position_of(i)], ("tile", t)
+    return first, got
+
+
+@pytest.mark.parametrize("run_len", [2 ** 31 + 1, 2 ** 32 + 1, 2 ** 32 + 2 ** 31 + 3, 2 ** 20 + 1])
+def test_tile_map_of_a_single_misaligned_run_beyond_32_bits(host_check, run_len):
+    """One contiguous shard that starts off a generator-block boundary takes the staging kernel with a
+    single run.  For runs of 2^31 elements and more the tile map has to clamp the run's bounds to the
+    tile BEFORE narrowing them: every slot of the first, last and 2^31 / 2^32-crossing tiles is written
+    exactly once, with the position of its own element."""
+    n = 2 * run_len                       # two ranks, chunk = run_len; rank 1 starts at run_len (odd: phase 1 or 3)
+    words = sharding_words([n], [2], [("S", 0)], [1])
+    offset = 1 << 36
+    probes = [e for e in (2 ** 31 - 1, 2 ** 31, 2 ** 32 - 1, 2 ** 32, 2 ** 32 + 2 ** 31) if e < run_len]
+    for big in (1, 0):
+        head, got = check_tiles(host_check, words, offset, 4, big, lambda i: np.uint64(offset + run_len) + i, run_len,
+                                probes)
+        assert head["wide"] == (1 if run_len >= 2 ** 30 else 0)
+        assert head["units_per_run"] == (run_len % 4 + run_len + 3) // 4
+
+
+def test_tile_map_of_column_shards_with_equal_and_unequal_phases(host_check):
+    """Ragged column shards (many runs): row lengths whose runs all start at the same phase (4100) and
+    at rotating phases (4101), 4- and 8-element units, narrow and wide index types."""
+    for rows, cols, unit_elems, big in ((16384, 4100, 4, 1), (16384, 4101, 4, 1), (4096, 4101, 8, 0), (300, 333, 4, 0),
+                                        (300, 333, 8, 0), (2 ** 20 + 3, 4101, 4, 1)):
+        words = sharding_words([rows, cols], [3], [("S", 1)], [1])
+        w = -(-cols // 3)                      # rank 1's columns [w, 2w)
+        offset = 4096
+
+        def position_of(i, w=w, cols=cols):
+            return np.uint64(offset) + (i // np.uint64(w)) * np.uint64(cols) + np.uint64(w) + i % np.uint64(w)
+
+        n = rows * w
+        head, _ = check_tiles(host_check, words, offset, unit_elems, big, position_of, n,
+                              [n // 2, n // 3, 2 ** 31] if n > 2 ** 31 else [n // 2, n // 3])
+        assert head["wide"] == (1 if n >= 2 ** 30 else 0)
