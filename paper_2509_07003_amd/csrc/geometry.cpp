@@ -316,6 +316,28 @@ LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offse
   return c;
 }
 
+bool plan_theta(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t unit_elems, ThetaPlan* tp) {
+  const uint64_t theta = g.virtual_threads, n = static_cast<uint64_t>(g.local_numel), V = unit_elems;
+  if (theta == 0 || !g.boxed || n == 0) return false;
+  if (rs.n_runs != 1 || rs.run_len != n) return false;          // one run only
+  if (theta % V != 0 || g.origin % V != 0) return false;        // units must not straddle threads or steps
+  // Step groups at the shard's two ends are only partly inside it; their threads still run.
+  // Below 16 step groups' worth of elements that waste exceeds a third: leave it to the element-wise kernel.
+  if (theta > (1ull << 40) || n / 64 < theta) return false;
+  const uint64_t first_step = g.origin / theta, last_step = (g.origin + n - 1) / theta;
+  tp->theta = theta;
+  tp->cols = theta / V;
+  tp->group0 = first_step / 4;
+  const uint64_t groups = last_step / 4 - tp->group0 + 1;
+  tp->total_threads = groups * tp->cols;
+  tp->narrow = (tp->total_threads < (1ull << 31) && tp->cols < (1ull << 31)) ? 1u : 0u;
+  tp->cols_div = tp->narrow ? make_div32(static_cast<uint32_t>(tp->cols)) : Div32{1, 0, 0};
+  tp->origin = g.origin;
+  tp->local_numel = n;
+  tp->block0 = offset / 4;
+  return true;
+}
+
 template <typename IT>
 PlanT<IT> make_plan(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t units_per_run) {
   PlanT<IT> p{};

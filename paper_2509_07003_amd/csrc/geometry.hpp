@@ -104,6 +104,28 @@ struct LaunchChoice {
 };
 LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offset, const LaunchTraits& traits);
 
+// ---- the virtual-thread layout with one generator call per four outputs ------------
+// Algorithm 1's (tau, beta) virtualisation puts element j at virtual thread tau = j mod Theta,
+// step s = j / Theta; word s mod 4 of block (offset / 4 + s / 4, tau).  The four words of one
+// block therefore belong to the elements j, j + Theta, j + 2 Theta, j + 3 Theta of one step group
+// (4 g <= s < 4 g + 4).  When the shard is ONE run [origin, origin + n) of the flattened global
+// tensor, Theta and origin are multiples of the unit and the run is many step groups long, a
+// thread can own the unit-wide column c of a step group g: unit_elems generator blocks feed its
+// four aligned units, one per step, and neighbouring threads write neighbouring units.
+struct ThetaPlan {
+  uint64_t theta = 0;          // Theta
+  uint64_t cols = 0;           // Theta / unit_elems: threads per step group
+  Div32 cols_div{};            // divides by cols (when narrow)
+  uint32_t narrow = 0;         // thread numbers and cols are below 2^31: 32-bit division
+  uint64_t group0 = 0;         // first step group that holds an element of the shard
+  uint64_t origin = 0;         // global flat index of local element 0
+  uint64_t local_numel = 0;
+  uint64_t block0 = 0;         // offset / 4: generator block of step group 0
+  uint64_t total_threads = 0;  // (number of step groups) * cols
+};
+// Fills `tp` and returns true when the shard qualifies; otherwise the element-wise kernel serves it.
+bool plan_theta(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t unit_elems, ThetaPlan* tp);
+
 // Largest tile (in units, a multiple of 8 so that tiles start on 128-byte lines) whose
 // generator blocks fit the workgroup's passes; 0 = runs too short for tiling.
 uint64_t pick_tile_units(uint64_t run_len, uint64_t unit_elems, uint64_t per_thread, bool phases_equal);

@@ -617,6 +617,83 @@ chain_kernel(const ChainPlan cp, const uint64_t offset, const uint64_t theta, co
   emit_element<OP, DT>(value, prm, xin, static_cast<int64_t>(i), out, mask);
 }
 
+// ---- virtual-thread layout, one generator call per four outputs ---------------------
+// Thread (g, c) owns column c (V consecutive virtual threads tau = c V .. c V + V - 1) of step
+// group g: V generator blocks, whose word k belongs to step 4 g + k, i.e. to the aligned unit
+// that starts at global index (4 g + k) Theta + c V.  Units outside the shard are skipped; the
+// shard's last unit may be partial.
+template <int OP, int DT>
+__global__ void __launch_bounds__(kThreads)
+theta_kernel(const ThetaPlan tp, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
+  constexpr int V = UnitOf<OP, DT>::kElems;
+  touch_params<OP>(prm);
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (t >= tp.total_threads) return;
+  uint64_t gi, c;
+  if (tp.narrow) {
+    const uint32_t q = tp.cols_div.div(static_cast<uint32_t>(t));
+    gi = q;
+    c = static_cast<uint32_t>(t) - q * static_cast<uint32_t>(tp.cols);
+  } else {
+    gi = t / tp.cols;
+    c = t - gi * tp.cols;
+  }
+  const uint64_t group = tp.group0 + gi;
+  const uint64_t block = tp.block0 + group;      // the same for all V virtual threads
+  const uint64_t tau0 = c * V;
+
+  // The four units of this thread: step 4 group + k starts at global index (4 group + k) Theta + tau0.
+  uint64_t unit[4];
+  bool inside[4], whole[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint64_t j = (4 * group + static_cast<uint64_t>(k)) * tp.theta + tau0;
+    // origin and j are multiples of V: a unit lies wholly below the shard or starts inside/above it.
+    const uint64_t i = j - tp.origin;
+    inside[k] = j >= tp.origin && i < tp.local_numel;
+    whole[k] = inside[k] && i + V <= tp.local_numel;
+    unit[k] = inside[k] ? i / V : 0;
+  }
+  u32x4 xv[4], rv[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    xv[k] = u32x4{0u, 0u, 0u, 0u};
+    rv[k] = u32x4{0u, 0u, 0u, 0u};
+    if constexpr (kIsDropout<OP>)
+      if (whole[k]) xv[k] = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + unit[k]);
+    if constexpr (OP == kOpDropoutAdd)
+      if (whole[k]) rv[k] = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + unit[k]);
+  }
+
+  // cv[e][k]: converted value of word k of virtual thread tau0 + e (for a normal the pairs are the
+  // words (0,1) and (2,3) of a block, i.e. steps 4 g, 4 g + 1 and 4 g + 2, 4 g + 3 of one thread).
+  uint32_t cv[V][4];
+#pragma unroll
+  for (int e = 0; e < V; ++e) {
+    const uint64_t tau = tau0 + static_cast<uint64_t>(e);
+    uint32_t d[4];
+    philox_rounds(static_cast<uint32_t>(block), static_cast<uint32_t>(block >> 32), static_cast<uint32_t>(tau),
+                  static_cast<uint32_t>(tau >> 32), prm.key0, prm.key1, d);
+    convert_block<OP, DT>(d, prm, cv[e]);
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (!inside[k]) continue;
+    uint32_t v[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = cv[e][k];
+    if (whole[k]) {
+      emit_unit<OP, DT>(v, prm, xv[k], rv[k], unit[k], out, mask);
+    } else {
+      const uint64_t i0 = unit[k] * V;
+#pragma unroll
+      for (int e = 0; e < V - 1; ++e)
+        if (i0 + static_cast<uint64_t>(e) < tp.local_numel)
+          emit_element<OP, DT>(v[e], prm, xin, static_cast<int64_t>(i0 + e), out, mask);
+    }
+  }
+}
+
 // Enqueues `kernel` and returns the launch's own status (hipGetLastError would also report,
 // and clear, an error some other code left behind).
 template <typename... Params, typename... Args>
@@ -718,6 +795,15 @@ hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, 
 template <int OP, int DT>
 hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
                      uint8_t* mask, hipStream_t stream) {
+  if (g.boxed && g.virtual_threads != 0) {
+    ThetaPlan tp;
+    if (plan_theta(g, run_shape(g), offset, UnitOf<OP, DT>::kElems, &tp)) {
+      const uint64_t blocks = (tp.total_threads + kThreads - 1) / kThreads;
+      if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+      return enqueue(theta_kernel<OP, DT>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), stream, tp, prm, x, out,
+                     mask);
+    }
+  }
   if (!g.boxed || g.virtual_threads != 0) return launch_chain<OP, DT>(g, offset, prm, x, out, mask, stream);
   const RunShape rs = run_shape(g);
   LaunchTraits traits;

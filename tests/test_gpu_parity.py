@@ -584,6 +584,63 @@ def test_virtual_thread_layout(theta):
         assert v.vesrng_advance_offset(sh1, offset) == oracle.advance_offset(shape, offset, None, theta)
 
 
+@pytest.mark.parametrize("theta", [4, 8, 64, 256, 4096])
+def test_virtual_thread_layout_one_generator_call_per_four_outputs(theta):
+    """Contiguous shards (unsharded tensors, row shards) that are many step groups long take the
+    kernel in which a thread owns a column of virtual threads and four steps: all four words of every
+    generator block are used.  Every operator and dtype against the oracle, ragged ends included."""
+    seed, offset = (0xFACE << 32) | 99, 1 << 35
+    cases = [([1000, 80], [1], [("R",)], [0]),                     # unsharded
+             ([1000, 80], [4], [("S", 0)], [2]),                   # row shard: origin 40000
+             ([999, 88], [3], [("S", 0)], [1]),                    # 333 rows: origin 29304, ragged length
+             ([262144 + 8 * 3 + 5], [1], [("R",)], [0]),           # 1-D, last unit partial
+             ([64, 4096 + 8], [2], [("S", 0)], [1])]
+    ran = 0
+    for shape, mesh, pls, c in cases:
+        args = (shape, mesh, pls, c, None, theta)
+        sh = v.Sharding(*args)
+        lshape, n = v.vesrng_local_shape(sh)
+        if n < 64 * theta:
+            continue
+        ran += 1
+        what = "theta=%d %s" % (theta, args[:4])
+        say(what)
+        assert np.array_equal(gpu_fill("raw", None, args, seed, offset), oracle.raw_u32(args, seed, offset, threads=THREADS)), what
+        assert np.array_equal(gpu_fill("randint", None, args, seed, offset, low=-7, high=1000),
+                              oracle.randint(args, -7, 1000, seed, offset, threads=THREADS)), what
+        for dtype in ("f32", "bf16", "f16"):
+            got = gpu_fill("uniform", dtype, args, seed, offset, low=-1.0, high=2.0)
+            want = oracle.uniform(args, DT[dtype][2], -1.0, 2.0, seed, offset, threads=THREADS)
+            assert_float_bits_equal(got, want, what + " uniform " + dtype, dtype=dtype)
+            got = gpu_fill("normal", dtype, args, seed, offset, mean=0.5, std=2.0)
+            check_normal(got, args, dtype, 0.5, 2.0, seed, offset, what + " normal " + dtype)
+            xf = W.adversarial_f32(n, seed=theta)
+            x = xf if dtype == "f32" else W.bits16_from_f32(xf, dtype)
+            y, m = gpu_dropout(dtype, args, 0.2, seed, offset, x)
+            yo, mo = oracle.dropout(args, DT[dtype][2], 0.2, seed, offset, x, threads=THREADS)
+            assert np.array_equal(m, mo), what
+            assert_float_bits_equal(y, yo, what + " dropout " + dtype, dtype=dtype)
+            y, _ = gpu_dropout(dtype, args, 0.2, seed, offset, x, with_mask=False, in_place=True)
+            assert_float_bits_equal(y, yo, what + " dropout in place " + dtype, dtype=dtype)
+        r = W.bf16_bits_from_f32(W.adversarial_f32(n, seed=theta + 1))
+        xb = W.bf16_bits_from_f32(xf)
+        yo, mo = oracle.dropout_add(args, oracle.BF16, 0.2, seed, offset, xb, r, threads=THREADS)
+        xd, rd = to_device(xb, "bf16"), to_device(r, "bf16")
+        yd = torch.empty_like(xd)
+        md = torch.empty(n, dtype=torch.uint8, device=DEV)
+        v.vesrng_dropout_add(sh, v.BF16, 0.2, seed, offset, xd, rd, yd, md)
+        torch.cuda.synchronize()
+        assert np.array_equal(md.cpu().numpy().reshape(lshape), mo), what
+        assert_float_bits_equal(to_host(yd, "bf16").reshape(lshape), yo, what + " dropout_add")
+    assert ran >= 1
+    # The shards of a row-sharded tensor merge to the unsharded tensor in this layout too.
+    shape, mesh, pls = [1024, 96], [4], [("S", 0)]
+    if 64 * theta <= 256 * 96:
+        shards = {c: gpu_fill("raw", None, (shape, mesh, pls, list(c), None, theta), seed, offset) for c in mesh_coords(mesh)}
+        single = gpu_fill("raw", None, (shape, [1], [("R",)], [0], None, theta), seed, offset)
+        assert np.array_equal(merge_shards(shards, mesh, pls), single)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_dropout_add_residual(dtype):
     """Fused dropout + residual add, aligned / tiled / element-wise kernels, in place on either input."""
@@ -785,6 +842,129 @@ def test_table5_sizes_5d_double_sharding(label, shape):
         yo, mo = oracle.dropout(args, oracle.BF16, 0.1, seed, offset, x, threads=THREADS)
         assert np.array_equal(m, mo), what
         assert_float_bits_equal(y, yo, what)
+
+
+def _table5_shardings(ndim=5):
+    """Every single shard dimension "#a" (1-D mesh of 4) and every ordered pair "#a and #b", a = b
+    included (2-D mesh 2 x 2): the sharding column of the paper's per-operator table."""
+    for a in range(ndim):
+        yield [4], [("S", a)], [a % 4]
+    for k, (a, b) in enumerate(itertools.product(range(ndim), repeat=2)):
+        yield [2, 2], [("S", a), ("S", b)], [k % 2, (k // 2) % 2]
+
+
+@pytest.mark.parametrize("ops", ["raw+randint", "uniform", "normal", "dropout"])
+def test_table5_full_double_sharding_grid_at_64mb(ops):
+    """The paper's micro-benchmark grid (App. C, Table 5) at its 64 MB point (2^24 fp32 elements, 5-D):
+    all 5 single and all 25 double shardings, every operator and dtype, one rank of each against the
+    threaded oracle element by element; a second shape with odd extents makes every shard ragged."""
+    seed, offset = 20250101, 1 << 30
+    even, odd = [16, 32, 32, 32, 32], [15, 33, 31, 34, 31]
+    assert int(np.prod(even)) * 4 == 64 << 20
+    count = 0
+    for shape in (even, odd):
+        for k, (mesh, pls, coord) in enumerate(_table5_shardings()):
+            args = (shape, mesh, pls, coord)
+            what = "%s %s" % (ops, args)
+            say(what)
+            light = shape is odd and k % 3 != 0      # the odd shape: every third sharding in full
+            if ops == "raw+randint":
+                assert np.array_equal(gpu_fill("raw", None, args, seed, offset),
+                                      oracle.raw_u32(args, seed, offset, threads=THREADS)), what
+                if not light:
+                    assert np.array_equal(gpu_fill("randint", None, args, seed, offset, low=-3, high=100000),
+                                          oracle.randint(args, -3, 100000, seed, offset, threads=THREADS)), what
+            elif ops == "uniform":
+                for dtype in ("f32", "bf16") + (("f16",) if k % 5 == 0 else ()):
+                    if light and dtype != "bf16":
+                        continue
+                    got = gpu_fill("uniform", dtype, args, seed, offset, low=-1.0, high=1.0)
+                    want = oracle.uniform(args, DT[dtype][2], -1.0, 1.0, seed, offset, threads=THREADS)
+                    assert_float_bits_equal(got, want, what + dtype, dtype=dtype)
+            elif ops == "normal":
+                for dtype in ("f32", "bf16") + (("f16",) if k % 5 == 1 else ()):
+                    if light and dtype != "f32":
+                        continue
+                    got = gpu_fill("normal", dtype, args, seed, offset, mean=0.0, std=0.02)
+                    check_normal(got, args, dtype, 0.0, 0.02, seed, offset, what + dtype)
+            else:
+                n = oracle.local_shape(*args)[1]
+                xf = np.random.default_rng(k).standard_normal(n, dtype=np.float32)
+                for dtype in ("bf16", "f32") + (("f16",) if k % 5 == 2 else ()):
+                    if light and dtype != "bf16":
+                        continue
+                    x = xf if dtype == "f32" else W.bits16_from_f32(xf, dtype)
+                    y, m = gpu_dropout(dtype, args, 0.1, seed, offset, x)
+                    yo, mo = oracle.dropout(args, DT[dtype][2], 0.1, seed, offset, x, threads=THREADS)
+                    assert np.array_equal(m, mo), what + dtype
+                    assert_float_bits_equal(y, yo, what + dtype, dtype=dtype)
+            count += 1
+    assert count == 60
+
+
+def _windows(n, width=20000):
+    """Sampled index windows of a local shard: both ends, the middle, and the 2^31 / 2^32 crossings."""
+    marks = [0, n // 3, n // 2, (1 << 31), (1 << 32), n - width]
+    out = []
+    for mk in marks:
+        b = max(0, min(n - width, mk - width // 2))
+        if all(abs(b - ob) >= width for ob, _ in out):
+            out.append((b, b + width))
+    return out
+
+
+@pytest.mark.parametrize("label,shape", [("1 GB", [32, 64, 32, 64, 64]), ("16 GB", [64, 64, 64, 128, 128])])
+def test_table5_large_tensors_on_sampled_windows(label, shape):
+    """The 1 GB and 16 GB points of the paper's table (2^28 and 2^32 fp32 elements): a nested shard of
+    one dimension, an interleaved shard, a ragged shard of the innermost dimension and a ragged nested
+    shard of two inner dimensions; fp32 uniform fill, fp32 normal fill and fused bf16 dropout, compared
+    with the oracle on sampled windows of the local shard (the oracle is scalar)."""
+    numel = int(np.prod(shape))
+    assert numel * 4 in (1 << 30, 16 << 30)
+    seed, offset = 424242, 1 << 37
+    cases = [([2, 4], [("S", 1), ("S", 1)], [1, 2]),               # "#1 and #1": nested, same dimension
+             ([8], [("IS", 1, 4)], [5]),                           # interleaved: heads dealt out in 4 groups
+             ([3], [("S", 4)], [1]),                               # ragged innermost dimension (64 or 128 over 3)
+             ([3, 3], [("S", 3), ("S", 4)], [2, 2])]               # "#3 and #4", both ragged
+    for mesh, pls, coord in cases:
+        args = (shape, mesh, pls, coord)
+        sh = v.Sharding(*args)
+        lshape, n = v.vesrng_local_shape(sh)
+        what = "%s %s (%d local elements)" % (label, args, n)
+        say(what)
+        wins = _windows(n)
+        out = torch.empty(n, dtype=torch.float32, device=DEV)
+        v.vesrng_uniform(sh, v.F32, 0.0, 1.0, seed, offset, out)
+        torch.cuda.synchronize()
+        for b, e in wins:
+            want = oracle.uniform(args, oracle.F32, 0.0, 1.0, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+            assert np.array_equal(out[b:e].cpu().numpy(), want), (what, b, e)
+        v.vesrng_normal(sh, v.F32, 0.0, 1.0, seed, offset, out)
+        torch.cuda.synchronize()
+        for b, e in wins:
+            ref = oracle.normal_f64_values(args, 0.0, 1.0, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+            err = np.abs(out[b:e].cpu().numpy().astype(np.float64) - ref)
+            assert (err <= 1e-6 * np.maximum(np.abs(ref), 1.0)).all(), (what, b, e)
+        del out
+        # Fused bf16 dropout: input made on the device, the windows copied to the host for the oracle.
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(n % 1000)
+        x = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+        x.normal_(generator=gen)
+        y = torch.empty_like(x)
+        mask = torch.empty(n, dtype=torch.uint8, device=DEV)
+        v.vesrng_dropout(sh, v.BF16, 0.1, seed, offset, x, y, mask)
+        torch.cuda.synchronize()
+        xh = np.zeros(n, dtype=np.uint16)               # untouched pages cost nothing
+        for b, e in wins:
+            xh[b:e] = x[b:e].view(torch.int16).cpu().numpy().view(np.uint16)
+        for b, e in wins:
+            yo, mo = oracle.dropout(args, oracle.BF16, 0.1, seed, offset, xh, i_begin=b, i_end=e)
+            assert np.array_equal(mask[b:e].cpu().numpy(), mo.reshape(-1)[b:e]), (what, b, e)
+            assert_float_bits_equal(y[b:e].view(torch.int16).cpu().numpy().view(np.uint16), yo.reshape(-1)[b:e], what)
+        keep = float(mask[:1 << 24].float().mean())
+        assert abs(keep - 0.9) < 1e-3
+        del x, y, mask, xh
 
 
 # ------------------------------------------------------------- binary16 -------
