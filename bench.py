@@ -10,6 +10,13 @@ are resident in HBM before the timed region.  The metric is algorithmic bytes pe
 (2 B read + 2 B written + 1 B mask per element).
 
 Prints ONE JSON line.  Only one GPU is used: --gpus above 1 is refused.
+
+Besides the headline the line carries, per workload config C1..C5, a roofline block built from
+ceilings MEASURED IN THE SAME RUN (plain store / copy / traffic-pattern kernels, the generator
+alone, and the issue rate of every instruction class the kernels are made of), steady-state rates
+of the operators whose own configs are too small to leave the launch-latency regime, and the CPU
+oracle timed on the host's cores.  `--design-choices` instead times every retained design choice
+against its alternative (same kernels, one choice flipped) and prints that as one JSON line.
 """
 import argparse
 import json
@@ -21,7 +28,31 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X published peak HBM bandwidth
+HBM_PEAK_GBS = 8000.0        # MI355X published peak HBM bandwidth
+SETTLE_SECONDS = 0.25        # untimed launches before any timed region: the first tens of milliseconds of GPU
+                             # work after an idle period run slower (clocks ramp up)
+
+# Vector-ALU instructions per wavefront of the kernels the workload configs run, by issue class.
+# Each lane of a wave produces one unit (4 fp32 or 8 bf16 elements).  Counts are those of the
+# compiler's listing of the kernel (hipcc -S), which for these straight-line kernels is what the
+# hardware counter SQ_INSTS_VALU / SQ_WAVES reads (profiles/counters_bench_kernels.txt);
+# tests/test_bench_model.py recounts them from a fresh listing.  "other" = everything that is
+# neither a Philox product (v_mad_u64_u32), a Philox XOR (v_bitop3_b32) nor a transcendental.
+KERNEL_MIX = {
+    "aligned normal bf16": {"kernel": "aligned_kernel<2, 1, unsigned int, 1>", "unit_elems": 8,
+                            "mad_u64_u32": 40, "bitop3_b32": 40, "trans": 16, "other": 65},
+    "aligned normal f32": {"kernel": "aligned_kernel<2, 0, unsigned int, 1>", "unit_elems": 4,
+                           "mad_u64_u32": 21, "bitop3_b32": 20, "trans": 8, "other": 39},
+    "aligned dropout bf16": {"kernel": "aligned_kernel<3, 1, unsigned int, 1>", "unit_elems": 8,
+                             "mad_u64_u32": 40, "bitop3_b32": 40, "trans": 0, "other": 76},
+    "aligned uniform f32": {"kernel": "aligned_kernel<1, 0, unsigned int, 0>", "unit_elems": 4,
+                            "mad_u64_u32": 19, "bitop3_b32": 20, "trans": 0, "other": 24},
+    "ragged normal f32": {"kernel": "ragged_kernel<2, 0, unsigned int, 1>", "unit_elems": 4,
+                          "mad_u64_u32": 22, "bitop3_b32": 20, "trans": 8, "other": 50},
+}
+SIMPLE_CLASSES = ["add_u32", "fma_f32", "mul_f32", "cvt_f32_u32", "cvt_pk_bf16_f32", "lshrrev_b32", "mul_lo_u32",
+                  "cmp_cndmask_b32"]
+TRANS_CLASSES = ["log_f32", "sqrt_f32", "sin_f32", "cos_f32"]
 
 
 def algorithmic_bytes(op, dtype, numel):
@@ -42,6 +73,39 @@ def read_traffic(workload_tag):
     except OSError:
         pass
     return None
+
+
+def settle(torch, fn, seconds=SETTLE_SECONDS):
+    """Runs fn() back to back until `seconds` of wall time have passed (synchronising every few
+    launches); returns (launches, seconds)."""
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        for _ in range(8):
+            fn()
+        n += 8
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if dt >= seconds:
+            return n, dt
+
+
+def burst_seconds(torch, fn, reps):
+    """Per-launch seconds of `reps` back-to-back launches between one HIP event pair on the current stream."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / reps
+
+
+def steady_seconds(torch, fn, nbytes, bursts=5):
+    """Median over `bursts` bursts (each about 10 ms of launches) after settling by time."""
+    settle(torch, fn)
+    reps = max(5, int(0.010 / max(nbytes / 5e12, 2e-6)))
+    return sorted(burst_seconds(torch, fn, reps) for _ in range(bursts))[bursts // 2], reps
 
 
 def make_launcher(v, W, torch, w, coord, copies=1):
@@ -71,23 +135,6 @@ def make_launcher(v, W, torch, w, coord, copies=1):
     return launch, n, algorithmic_bytes(w.op, w.dtype, n)
 
 
-def time_kernel(torch, launch, steps, warmup):
-    """Average launch duration from HIP events recorded on the launch stream around each call."""
-    for k in range(warmup):
-        launch(k)
-    torch.cuda.synchronize()
-    pairs = []
-    for k in range(steps):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        launch(k)
-        b.record()
-        pairs.append((a, b))
-    torch.cuda.synchronize()
-    ms = sorted(a.elapsed_time(b) for a, b in pairs)
-    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
-
-
 def time_batch(torch, launch, reps, warmup):
     """Average duration of back-to-back launches (one event pair around the whole batch):
     for kernels of a few microseconds, where a per-launch event pair would dominate."""
@@ -104,7 +151,7 @@ def time_batch(torch, launch, reps, warmup):
 
 
 def time_graph(torch, launch, reps):
-    """Per-launch time of `reps` back-to-back launches replayed from a captured HIP graph: the
+    """Per-launch milliseconds of `reps` back-to-back launches replayed from a captured HIP graph: the
     GPU-side cost without the host's issue rate (the library only enqueues kernels, so its calls
     can be captured)."""
     side = torch.cuda.Stream()
@@ -117,10 +164,9 @@ def time_graph(torch, launch, reps):
             for k in range(reps):
                 launch(k)
     torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
+    settle(torch, graph.replay, 0.1)
     times = []
-    for _ in range(5):
+    for _ in range(7):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         graph.replay()
@@ -130,10 +176,24 @@ def time_graph(torch, launch, reps):
     return sorted(times)[len(times) // 2]
 
 
+def measured_clock(B, torch):
+    """Shader clock under load from the two on-chip counters (shader ticks / constant-rate wall ticks)."""
+    wall_khz = B.vesrng_bench_device_info()[4]
+    ticks = torch.zeros(4, dtype=torch.int64, device="cuda")
+    best = 0.0
+    for _ in range(3):
+        B.vesrng_bench_clock(200000, ticks)
+        torch.cuda.synchronize()
+        t = ticks.cpu().tolist()
+        if t[1] > 0:
+            best = max(best, t[0] / t[1] * wall_khz * 1e3)
+    return best
+
+
 def measured_ceilings(B, torch):
-    """Rates of the plain probe kernels on this machine, in this run: what bare 128-bit stores,
-    a 16-byte copy, the dropout kernel's access pattern without arithmetic, and the generator
-    alone can reach.  1 GiB buffers (beyond the 256 MB last-level cache)."""
+    """Rates of the plain probe kernels on this machine, in this run: what bare 128-bit stores (aligned and
+    element-aligned), a 16-byte copy, the dropout kernel's access pattern without arithmetic, the generator
+    alone and every instruction class can reach.  1 GiB buffers (beyond the 256 MB last-level cache)."""
     nbytes = 1 << 30
     units = nbytes // 16
     a = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda")
@@ -141,46 +201,93 @@ def measured_ceilings(B, torch):
     m = torch.empty(nbytes // 8, dtype=torch.int32, device="cuda")
     blocks = 1 << 30
 
-    def med(fn):
-        return time_kernel(torch, lambda _k: fn(), 20, 3)[1] * 1e-3
+    def rate(fn, work):
+        return work / steady_seconds(torch, fn, nbytes)[0] / 1e9
 
-    t_store = med(lambda: B.vesrng_bench_probe(B.PROBE_STORE, units, None, a))
-    t_copy = med(lambda: B.vesrng_bench_probe(B.PROBE_COPY, units, a, b))
-    t_mix = med(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m))
-    t_gen = med(lambda: B.vesrng_bench_probe(B.PROBE_PHILOX, blocks, None, a))
-    return {"store_only_gb_per_s": nbytes / t_store / 1e9, "copy_gb_per_s": 2 * nbytes / t_copy / 1e9,
-            "dropout_traffic_gb_per_s": 2.5 * nbytes / t_mix / 1e9,
-            "philox_only_gblocks_per_s": blocks / t_gen / 1e9,
-            "note": "plain probe kernels of libvesrng_bench.so (vesrng_bench_probe), medians of 20 launches in this run"}
+    out = {"store_only_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_STORE, units, None, a), nbytes),
+           "store_unaligned_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_STORE_UNALIGNED, units, None, a), nbytes),
+           "copy_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_COPY, units, a, b), 2 * nbytes),
+           "dropout_traffic_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
+           "philox_only_gblocks_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_PHILOX, blocks, None, a), blocks)}
+    # Issue rates: cycles a SIMD needs per wave-instruction of each class, 16 workgroups per compute unit.
+    cus, sclk_khz = B.vesrng_bench_device_info()[:2]
+    clock_hz = measured_clock(B, torch) or sclk_khz * 1e3
+    wgs, iters = cus * 16, 1000
+    cycles = {}
+    for cls, name in enumerate(B.ALU_CLASSES):
+        secs = steady_seconds(torch, lambda: B.vesrng_bench_alu(cls, wgs, iters, a), 1 << 34, bursts=3)[0]
+        per_simd = wgs * 4 * iters * 64 * (2 if name == "cmp_cndmask_b32" else 1) / (cus * 4)
+        cycles[name] = secs * clock_hz / per_simd
+    out["shader_clock_mhz_measured"] = clock_hz / 1e6
+    out["issue_cycles_per_wave_instruction"] = cycles
+    out["note"] = ("plain kernels of libvesrng_bench.so (vesrng_bench_probe / vesrng_bench_alu), medians of 5 bursts of about "
+                   "10 ms each in this run; issue cycles are per SIMD at the measured shader clock")
+    return out
 
 
-SETTLE = 60                        # untimed launches before the timed region, at least (see main)
-VALU_PEAK = 256 * 4 * 32 * 2.4e9   # lane-operations/s: 256 CUs x 4 SIMDs x 32 lanes/cycle x 2.4 GHz
-                                   # (= the published 157.3 TFLOP/s fp32 vector rate / 2 flops per FMA)
+def issue_model_seconds(mix, units, ceil, cus):
+    """Time the vector ALUs need to issue a kernel's instructions: per wave, every class's count times its
+    measured issue cycles; waves spread over all SIMDs; at the measured shader clock."""
+    cyc = ceil["issue_cycles_per_wave_instruction"]
+    simple = sum(cyc[c] for c in SIMPLE_CLASSES) / len(SIMPLE_CLASSES)
+    trans = sum(cyc[c] for c in TRANS_CLASSES) / len(TRANS_CLASSES)
+    per_wave = (mix["mad_u64_u32"] * cyc["mad_u64_u32"] + mix["bitop3_b32"] * cyc["bitop3_b32"]
+                + mix["trans"] * trans + mix["other"] * simple)
+    waves = (units + 63) // 64
+    return waves / (cus * 4) * per_wave / (ceil["shader_clock_mhz_measured"] * 1e6), per_wave
 
 
-def steady_state(v, W, torch):
+def roofline_block(op, kernel_tag, nbytes, numel, seconds, floor_s, ceil, cus, ragged=False):
+    """Per-config roofline: achieved GB/s against the HBM peak, and against a model
+    t = launch floor + max(memory time at the measured ceiling of the kernel's own store / traffic
+    form, issue time of its instruction mix); `bound` names the largest of the three terms."""
+    mix = KERNEL_MIX[kernel_tag]
+    mem_ceiling = (ceil["dropout_traffic_gb_per_s"] if op == "dropout"
+                   else ceil["store_unaligned_gb_per_s"] if ragged else ceil["store_only_gb_per_s"])
+    t_mem = nbytes / (mem_ceiling * 1e9)
+    t_alu, per_wave = issue_model_seconds(mix, (numel + mix["unit_elems"] - 1) // mix["unit_elems"], ceil, cus)
+    terms = {"launch": floor_s, "hbm" if not ragged else "store-alignment": t_mem, "alu": t_alu}
+    bound = max(terms, key=terms.get)
+    t_model = floor_s + max(t_mem, t_alu)
+    achieved = nbytes / seconds / 1e9
+    return {"bound": bound, "kernel": "vesrng::" + mix["kernel"], "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "kernel_us": seconds * 1e6,
+            "model_us": {"launch_floor": floor_s * 1e6, "memory_at_measured_ceiling": t_mem * 1e6, "alu_issue": t_alu * 1e6,
+                         "total": t_model * 1e6},
+            "memory_ceiling_gb_per_s": mem_ceiling, "issue_cycles_per_wave": per_wave,
+            "frac_of_model": t_model / seconds,
+            "frac_of_measured_memory_ceiling": achieved / mem_ceiling,
+            "frac_of_measured_issue_model": t_alu / seconds}
+
+
+def steady_state(v, W, torch, ceil, cus):
     """The operators of the small configs at 64x the shard (same shapes of run), where launch latency
-    no longer dominates: C2's ragged fp32 normal fill (at this size the library stages it through LDS
-    with the large tile instead of using C2's own ragged kernel) and C3's bf16 normal fill (same
-    kernel as C3).  The bf16 fill is ALU-bound; its roofline is the vector issue rate (VALU
-    instructions per element from profiles/counters_bench_kernels.txt)."""
+    no longer dominates: C2's ragged fp32 normal fill and C3's bf16 normal fill (their own kernels), each
+    against its measured ceilings; and the virtual-thread layout on an unsharded tensor."""
     import copy
     res = {}
-    for wl, scale_dim, valu_per_elem in ((W.C2, 0, None), (W.C3, 0, 161.0 / 8)):
+    for wl, tag, ragged in ((W.C2, "ragged normal f32", True), (W.C3, "aligned normal bf16", False)):
         big = copy.deepcopy(wl)
         big.global_shape = list(wl.global_shape)
-        big.global_shape[scale_dim] *= 64
+        big.global_shape[0] *= 64
         launch, numel, nb = make_launcher(v, W, torch, big, wl.bench_coord, 1)
-        avg, med, mn = time_kernel(torch, launch, 20, 3)
-        gbs = nb / (med * 1e-3) / 1e9
-        r = {"workload": "%s with dim %d x64 (beyond the 256 MB last-level cache): shard of %d elements" % (wl.name, scale_dim, numel),
-             "median_launch_us": med * 1e3, "gb_per_s": gbs, "pct_hbm_peak": 100 * gbs / HBM_PEAK_GBS,
-             "gsamples_per_s": numel / (med * 1e-3) / 1e9}
-        if valu_per_elem is not None:
-            lane_ops = valu_per_elem * numel / (med * 1e-3)
-            r.update({"valu_lane_ops_per_s": lane_ops, "pct_valu_issue_peak": 100 * lane_ops / VALU_PEAK})
+        secs, reps = steady_seconds(torch, lambda: launch(0), nb)
+        r = {"workload": "%s with dim 0 x64 (beyond the 256 MB last-level cache): shard of %d elements" % (wl.name, numel),
+             "launches_per_burst": reps, "gb_per_s": nb / secs / 1e9, "pct_hbm_peak": 100 * nb / secs / 1e9 / HBM_PEAK_GBS,
+             "gsamples_per_s": numel / secs / 1e9,
+             "roofline": roofline_block(wl.op, tag, nb, numel, secs, 0.0, ceil, cus, ragged=ragged)}
+        r["pct_of_measured_store_ceiling"] = 100 * r["gb_per_s"] / ceil["store_only_gb_per_s"]
+        r["pct_of_measured_generator_ceiling"] = 100 * (r["gsamples_per_s"] / 4) / ceil["philox_only_gblocks_per_s"]
         res[wl.name.split()[0] + "x64"] = r
+    n = 1 << 28
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    for theta in (1 << 20, 0):
+        sh = v.Sharding([n], [1], [("R",)], [0], None, theta)
+        secs, reps = steady_seconds(torch, lambda: v.vesrng_uniform(sh, v.F32, 0.0, 1.0, 1, 0, out), 4 * n)
+        res["uniform_f32_2^28_theta_%d" % theta] = {
+            "workload": "fp32 uniform fill of an unsharded 2^28-element tensor, " +
+                        ("Algorithm 1's virtual-thread layout with 2^20 threads" if theta else "flat stream"),
+            "gb_per_s": 4 * n / secs / 1e9, "pct_hbm_peak": 100 * 4 * n / secs / 1e9 / HBM_PEAK_GBS}
     return res
 
 
@@ -220,6 +327,144 @@ def cpu_baseline(torch, W, w, coord, x_dev, sample):
             "cpu_model": cpu_model(), "logical_cpus_visible": os.cpu_count()}
 
 
+def counters_pass(v, W, torch):
+    """A lean pass for hardware-counter collection (rocprofv3 --pmc): every kernel the benchmark times is
+    launched a few times, eagerly and one after the other - no graph replay, no settling loops, no probes -
+    and the launches are listed in order, so that a counter row can be matched to its workload by kernel name
+    and grid size."""
+    import copy
+    log = []
+
+    def run(label, fn, times=3):
+        for _ in range(times):
+            fn()
+        torch.cuda.synchronize()
+        log.append({"workload": label, "launches": times})
+
+    for wl in (W.C1, W.C2, W.C3, W.C4, W.C5, W.C5_INTERLEAVED):
+        launch, numel, nb = make_launcher(v, W, torch, wl, wl.bench_coord, 1)
+        run("%s: %d elements, %d algorithmic bytes" % (wl.name, numel, nb), lambda: launch(0), 5 if wl is W.C5 else 3)
+        del launch
+    for wl in (W.C2, W.C3):
+        big = copy.deepcopy(wl)
+        big.global_shape = list(wl.global_shape)
+        big.global_shape[0] *= 64
+        launch, numel, nb = make_launcher(v, W, torch, big, wl.bench_coord, 1)
+        run("%s x64: %d elements, %d algorithmic bytes" % (wl.name.split()[0], numel, nb), lambda: launch(0))
+        del launch
+    n = 1 << 28
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    for theta in (1 << 20, 0):
+        sh = v.Sharding([n], [1], [("R",)], [0], None, theta)
+        run("fp32 uniform fill of 2^28 elements, virtual threads = %d" % theta,
+            lambda: v.vesrng_uniform(sh, v.F32, 0.0, 1.0, 1, 0, out))
+    return log
+
+
+# ---------------------------------------------------------------- design choices ----
+def design_choices(v, B, W, torch, once=False):
+    """Every design choice the kernels kept, timed against its alternative in this run: the same
+    kernels with one choice flipped (the variant libraries), or the plain probe kernels.  Per entry:
+    median microseconds per launch of 5 bursts, after settling, and GB/s of algorithmic bytes."""
+    res = {}
+
+    def entry(name, choice, cases):
+        rows = {}
+        for label, fn, nbytes in cases:
+            if once:      # counter collection: three eager launches, nothing timed
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                rows[label] = {"launches": 3}
+                continue
+            secs, reps = steady_seconds(torch, fn, nbytes)
+            rows[label] = {"us_per_launch": secs * 1e6, "gb_per_s": nbytes / secs / 1e9, "launches_per_burst": reps}
+        res[name] = {"choice": choice, "measured": rows}
+
+    nbytes = 1 << 30
+    units = nbytes // 16
+    a = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    m = torch.empty(nbytes // 8, dtype=torch.int32, device="cuda")
+    probe = B.vesrng_bench_probe
+    entry("launch shape", "one 16-byte unit per thread, one-shot grid",
+          [("one-shot (kept)", lambda: probe(B.PROBE_STORE, units, None, a), nbytes),
+           ("grid-stride loop, 8 workgroups per CU", lambda: probe(B.PROBE_STORE_GRID_STRIDE, units, None, a), nbytes),
+           ("four units per thread", lambda: probe(B.PROBE_STORE_4_PER_THREAD, units, None, a), nbytes)])
+    entry("store cache-control bits (store only)", "global_store_dwordx4 sc1 nt",
+          [("sc1 nt (kept)", lambda: probe(B.PROBE_STORE, units, None, a), nbytes),
+           ("nt", lambda: probe(B.PROBE_STORE_NT, units, None, a), nbytes),
+           ("plain", lambda: probe(B.PROBE_STORE_PLAIN, units, None, a), nbytes),
+           ("nt, element-aligned addresses", lambda: probe(B.PROBE_STORE_UNALIGNED, units, None, a), nbytes)])
+    entry("store cache-control bits (dropout traffic pattern)", "sc1 nt on both stores",
+          [("sc1 nt (kept)", lambda: probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
+           ("nt", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_NT, units, a, b, m), 2.5 * nbytes)])
+    blocks = 1 << 30
+    entry("three-way XOR of the generator (generator only)", "v_bitop3_b32",
+          [("v_bitop3_b32 (kept)", lambda: probe(B.PROBE_PHILOX, blocks, None, a), blocks * 16),
+           ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
+    del a, b, m
+
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "ragged", "realign", "smalltile", "bigtile")}
+    # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
+    w = W.C5
+    sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
+    shape, n5 = v.vesrng_local_shape(sh5)
+    x = W.device_activations(shape, w.input_seed, w.input_kind, w.dtype).reshape(-1)
+    y = torch.empty_like(x)
+    mask = torch.empty(n5, dtype=torch.uint8, device="cuda")
+    drop = lambda L: (lambda: L.vesrng_dropout(sh5, v.BF16, 0.1, 1234, 0, x, y, mask))
+    entry("C5 fused dropout: argument-fetch pinning, store bits", "pinned, sc1 nt",
+          [("library (kept)", drop(v), 5 * n5), ("without the pinning", drop(variants["nopin"]), 5 * n5),
+           ("plain non-temporal stores", drop(variants["ntstore"]), 5 * n5)])
+    del x, y, mask
+    n = 1 << 28
+    shu = v.Sharding([n], [1], [("R",)], [0])
+    o = torch.empty(n, dtype=torch.float32, device="cuda")
+    uni = lambda L: (lambda: L.vesrng_uniform(shu, v.F32, 0.0, 1.0, 1, 0, o))
+    entry("aligned fp32 uniform fill (2^28 elements): argument-fetch pinning, store bits", "pinned, sc1 nt",
+          [("library (kept)", uni(v), 4 * n), ("without the pinning", uni(variants["nopin"]), 4 * n),
+           ("plain non-temporal stores", uni(variants["ntstore"]), 4 * n)])
+    sh3 = v.Sharding([4096 * 64, 14336], [2, 4], [("S", 0), ("S", 1)], [1, 2])
+    n3 = v.vesrng_local_shape(sh3)[1]
+    ob = torch.empty(n3, dtype=torch.bfloat16, device="cuda")
+    nrm = lambda L: (lambda: L.vesrng_normal(sh3, v.BF16, 0.0, 0.02, 3, 0, ob))
+    entry("C3 x64 bf16 normal fill: three-way XOR", "v_bitop3_b32",
+          [("library (kept)", nrm(v), 2 * n3), ("two v_xor_b32", nrm(variants["twoxor"]), 2 * n3)])
+    del ob
+    # The pinning is about the latency of a workgroup's life: it shows on the small configs (GPU-side time per
+    # launch, replayed from a HIP graph), not on shards that keep the chip busy for hundreds of microseconds.
+    for wl, copies in ((W.C1, 256), (W.C3, 32), (W.C4, 8)):
+        rows = {}
+        for label, lib in (("library (kept)", v), ("without the pinning", variants["nopin"])):
+            launch, numel, nb = make_launcher(lib, W, torch, wl, wl.bench_coord, 1 if once else copies)
+            if once:
+                for k in range(3):
+                    launch(k)
+                torch.cuda.synchronize()
+                rows[label] = {"launches": 3}
+                continue
+            ms = sorted(time_graph(torch, launch, 4 * copies) for _ in range(3))[1]
+            rows[label] = {"us_per_launch": ms * 1e3, "gb_per_s": nb / (ms * 1e-3) / 1e9, "launches_per_burst": 4 * copies}
+        res["%s (graph replay): argument-fetch pinning" % wl.name.split()[0]] = {"choice": "pinned", "measured": rows}
+    # Ragged column shards [rows, 4096] cut three ways (C2's shape of run), two sizes.
+    for rows in (16384, 98304):
+        shr = v.Sharding([rows, 4096], [3], [("S", 1)], [1])
+        nr = v.vesrng_local_shape(shr)[1]
+        oi = o[:nr].view(torch.int32)
+        of = o[:nr]
+        for op, call in (("raw", lambda L: (lambda: L.vesrng_raw_u32(shr, 1, 0, oi))),
+                         ("fp32 uniform", lambda L: (lambda: L.vesrng_uniform(shr, v.F32, 0.0, 1.0, 1, 0, of))),
+                         ("fp32 normal", lambda L: (lambda: L.vesrng_normal(shr, v.F32, 0.0, 1.0, 1, 0, of)))):
+            entry("ragged %s fill, %d elements" % (op, nr), "large tile for raw and uniform from 2^23 elements, no staging for normal",
+                  [("library (kept)", call(v), 4 * nr),
+                   ("no staging, element-aligned stores", call(variants["ragged"]), 4 * nr),
+                   ("no staging, realigned across lanes (DPP)", call(variants["realign"]), 4 * nr),
+                   ("staged, small tile", call(variants["smalltile"]), 4 * nr),
+                   ("staged, large tile", call(variants["bigtile"]), 4 * nr)])
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +474,11 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the per-config side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known size) to scale rocprofv3's byte counters")
+    ap.add_argument("--design-choices", action="store_true",
+                    help="time every retained design choice against its alternative instead of the benchmark")
+    ap.add_argument("--counters-pass", action="store_true",
+                    help="for rocprofv3 --pmc: launch every timed kernel a few times, eagerly, and time nothing "
+                         "(with --design-choices: every choice and its alternative)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (mesh ranks are emulated on it); --gpus above 1 is not supported")
@@ -240,6 +490,13 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+
+    if a.design_choices:
+        print(json.dumps({"design_choices": design_choices(v, B, W, torch, once=a.counters_pass)}), flush=True)
+        return
+    if a.counters_pass:
+        print(json.dumps({"counters_pass": counters_pass(v, W, torch)}), flush=True)
+        return
 
     w, coord = W.C5, W.C5.bench_coord
     sh = v.Sharding(*w.sharding_args(coord))
@@ -254,47 +511,41 @@ def main():
         v.vesrng_dropout(sh, v.BF16, w.params["p"], w.seed, state["offset"], x, y, mask)
         state["offset"] = v.vesrng_advance_offset(sh, state["offset"])
 
-    # The first ~20 ms of GPU work after an idle period (and the first touch of 2.5 GB of buffers)
-    # run about 1.5 % slower: whatever --warmup says, at least SETTLE untimed launches come first.
-    settle = max(0, SETTLE - a.warmup)
-    for _ in range(settle):
-        v.vesrng_dropout(sh, v.BF16, w.params["p"], w.seed, 0, x, y, mask)
+    # Settle by TIME, whatever --warmup says: at least SETTLE_SECONDS of untimed launches come first.
+    settle_launches, settle_s = settle(torch, step)
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    # The timed region.  Every tenth launch (at least five of them) sits between two HIP events recorded on the launch
-    # stream (no host synchronisation inside the region), so the dominant kernel's duration is
-    # measured on launches that are part of `value`; bracketing every launch would put two more
-    # packets between each pair of kernels and cost `value` about 1.5 %.
-    every = max(1, min(10, a.steps // 5))
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range((a.steps + every - 1) // every)]
+    # The timed region: K steps between two HIP events recorded on the launch stream (and between two
+    # host clock readings after a synchronise).  No event sits between launches - a pair around each one
+    # adds packets that slow the stream - so the kernel's average duration is the events' elapsed time / K:
+    # it includes the few hundred nanoseconds between consecutive kernels, i.e. it can only overstate the
+    # kernel's own duration (rocprofv3's per-kernel average for the same command is slightly shorter).
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    e0.record()
     for k in range(a.steps):
-        if k % every == 0:
-            ea, eb = pairs[k // every]
-            ea.record()
-            step()
-            eb.record()
-        else:
-            step()
+        step()
+    e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / a.steps
     value = nbytes / (wall / a.steps) / 1e9
-    launch_ms = sorted(ea.elapsed_time(eb) for ea, eb in pairs)
-    avg_ms, med_ms, min_ms = sum(launch_ms) / len(launch_ms), launch_ms[len(launch_ms) // 2], launch_ms[0]
+    avg_ms = e0.elapsed_time(e1) / a.steps
     achieved = nbytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "vesrng::aligned_kernel<3 (dropout), 1 (bf16), unsigned int, 1 run axis>", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("c5_dropout_bf16"),
-                "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "min_launch_ms": min_ms,
+    roofline = {"bound": "hbm", "kernel": "vesrng::aligned_kernel<3 (dropout), 1 (bf16), unsigned int, 1 run axis>",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": read_traffic("c5_dropout_bf16"), "avg_launch_ms": avg_ms,
+                "timing": "HIP events on the launch stream around the %d launches of the timed region, elapsed / %d "
+                          "(includes the gaps between consecutive kernels)" % (a.steps, a.steps),
                 "algorithmic_bytes_per_launch": nbytes}
 
     out = {"metric": "sharded RNG fill / fused dropout GB/s per MI355X and % of HBM peak", "value": value,
            "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "u32 Philox + f32 scale, bf16 in/out, u8 mask", "data": "synthetic",
-           "config": {"workload": w.name, "rank": coord, "local_shape": shape, "elements": n, "settle_launches": settle,
+           "config": {"workload": w.name, "rank": coord, "local_shape": shape, "elements": n,
+                      "settle_launches": settle_launches, "settle_seconds": settle_s,
                       "gsamples_per_s": n / (wall / a.steps) / 1e9, "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBS},
            "roofline": roofline}
 
@@ -320,25 +571,43 @@ def main():
         del x, y, mask
         ceil = measured_ceilings(B, torch)
         out["ceilings"] = ceil
+        # Vector-ALU peak of this path: every instruction class the kernels use issues one wave-instruction
+        # per SIMD every ~4 cycles (16 lanes per cycle; transcendentals every ~8): lanes x clock.
+        ceil["valu_peak_lane_ops_per_s"] = cus * 4 * 16 * ceil["shader_clock_mhz_measured"] * 1e6
         roofline["frac_of_measured_traffic_ceiling"] = achieved / ceil["dropout_traffic_gb_per_s"]
         roofline["frac_of_measured_generator_ceiling"] = (n / 4 / (avg_ms * 1e-3) / 1e9) / ceil["philox_only_gblocks_per_s"]
+        t_alu, per_wave = issue_model_seconds(KERNEL_MIX["aligned dropout bf16"], n // 8, ceil, cus)
+        roofline["frac_of_measured_issue_model"] = t_alu / (avg_ms * 1e-3)
+        # Launch floor: graph replay of the same entry point on a shard of one workgroup.
+        tiny = v.Sharding([1024], [1], [("R",)], [0])
+        tbuf = torch.empty(1024, dtype=torch.float32, device="cuda")
+        floor_ms = time_graph(torch, lambda k: v.vesrng_uniform(tiny, v.F32, 0.0, 1.0, 1, 0, tbuf), 64)
+        ceil["launch_floor_us"] = floor_ms * 1e3
         extra = {}
+        tags = {"C1": ("aligned uniform f32", False), "C2": ("ragged normal f32", True), "C3": ("aligned normal bf16", False),
+                "C4": ("aligned dropout bf16", False), "C5i": ("aligned dropout bf16", False)}
         for wl, copies in ((W.C1, 256), (W.C2, 16), (W.C3, 32), (W.C4, 8), (W.C5_INTERLEAVED, 1)):
+            key = wl.name.split()[0] + ("i" if wl is W.C5_INTERLEAVED else "")
             launch, numel, nb = make_launcher(v, W, torch, wl, wl.bench_coord, copies)
             avg = time_batch(torch, launch, max(50, a.steps), 5)
             per_launch_graph = time_graph(torch, launch, 4 * copies if copies > 1 else 8)
-            extra[wl.name.split()[0] + ("i" if wl is W.C5_INTERLEAVED else "")] = {
+            tag, ragged = tags[key]
+            extra[key] = {
                 "graph_replay_us_per_launch": per_launch_graph * 1e3,
                 "graph_replay_gb_per_s": nb / (per_launch_graph * 1e-3) / 1e9,
                 "workload": wl.name, "elements": numel, "algorithmic_bytes": nb, "avg_launch_us": avg * 1e3,
                 "gb_per_s": nb / (avg * 1e-3) / 1e9, "gsamples_per_s": numel / (avg * 1e-3) / 1e9,
                 "pct_hbm_peak": 100 * nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, "buffers_cycled": copies,
-                "note": "back-to-back launches incl. host call overhead; buffers cycled to exceed the last-level cache"}
+                "note": "avg_launch_us: back-to-back launches incl. host call overhead; graph_replay: the same launches "
+                        "replayed from a HIP graph (GPU-side time per launch, the roofline block's kernel time); "
+                        "buffers cycled to exceed the last-level cache",
+                "roofline": roofline_block(wl.op, tag, nb, numel, per_launch_graph * 1e-3, floor_ms * 1e-3, ceil, cus,
+                                           ragged=ragged)}
+        extra["C5"] = {"workload": w.name, "elements": n, "algorithmic_bytes": nbytes,
+                       "roofline": roofline_block("dropout", "aligned dropout bf16", nbytes, n, avg_ms * 1e-3, floor_ms * 1e-3,
+                                                  ceil, cus)}
         out["per_config"] = extra
-        out["steady_state"] = steady_state(v, W, torch)
-        for r in out["steady_state"].values():
-            r["pct_of_measured_store_ceiling"] = 100 * r["gb_per_s"] / ceil["store_only_gb_per_s"]
-            r["pct_of_measured_generator_ceiling"] = 100 * (r["gsamples_per_s"] / 4) / ceil["philox_only_gblocks_per_s"]
+        out["steady_state"] = steady_state(v, W, torch, ceil, cus)
     print(json.dumps(out), flush=True)
 
 

@@ -5,7 +5,8 @@ module; the product binding does not.  Nothing is computed here.
 import ctypes as C
 
 from . import build as _build
-from .binding import _check, _dev, _stream, load_library
+from .binding import (BF16, F16, F32, Sharding, _check, _dev, _stream, load_library, vesrng_advance_offset,
+                      vesrng_local_shape)
 
 # vesrng_probe_kind
 (PROBE_STORE, PROBE_COPY, PROBE_DROPOUT_TRAFFIC, PROBE_PHILOX, PROBE_STORE_NT, PROBE_STORE_PLAIN,
@@ -64,6 +65,16 @@ class Variant:
     def __init__(self, name):
         self.name = name
         self._lib = load_library(_build.ensure("variant_" + name))
+
+    # What make_launcher-style callers need from the product binding, so that a variant can stand in for it.
+    Sharding = Sharding
+    F32, BF16, F16 = F32, BF16, F16
+
+    def vesrng_local_shape(self, sharding):
+        return vesrng_local_shape(sharding)
+
+    def vesrng_advance_offset(self, sharding, offset):
+        return vesrng_advance_offset(sharding, offset)
 
     def vesrng_raw_u32(self, sharding, seed, offset, out, stream=None):
         _check(self._lib.vesrng_raw_u32(C.byref(sharding.c), seed, offset, _dev(out), _stream(stream, out)))

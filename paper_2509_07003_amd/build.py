@@ -40,11 +40,16 @@ TARGETS = {
     # Three-way XORs of the generator as two v_xor_b32.
     "variant_twoxor": {"lib": "libvesrng_variant_twoxor.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=twoxor", "VESRNG_PHILOX_BITOP3=0"]},
-    # The staging kernel always with the small tile / always with the large tile.
+    # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
+    "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
+                       "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},
+    "variant_realign": {"lib": "libvesrng_variant_realign.so", "sources": PRODUCT_SOURCES,
+                        "defines": ["VESRNG_VARIANT_TAG=realign", "VESRNG_TILING=0", "VESRNG_RAGGED_DPP_REALIGN=1"]},
+    # Ragged shards: every operator staged, always with the small tile / with the large tile where there is one.
     "variant_smalltile": {"lib": "libvesrng_variant_smalltile.so", "sources": PRODUCT_SOURCES,
-                          "defines": ["VESRNG_VARIANT_TAG=smalltile", "VESRNG_BIG_TILE_MIN_ELEMS=(1ull<<62)"]},
+                          "defines": ["VESRNG_VARIANT_TAG=smalltile", "VESRNG_TILING=1", "VESRNG_BIG_TILE_MIN_ELEMS=(1ull<<62)"]},
     "variant_bigtile": {"lib": "libvesrng_variant_bigtile.so", "sources": PRODUCT_SOURCES,
-                        "defines": ["VESRNG_VARIANT_TAG=bigtile", "VESRNG_BIG_TILE_MIN_ELEMS=0ull"]},
+                        "defines": ["VESRNG_VARIANT_TAG=bigtile", "VESRNG_TILING=2", "VESRNG_BIG_TILE_MIN_ELEMS=0ull"]},
 }
 LIB = os.path.join(HERE, TARGETS["vesrng"]["lib"])
 

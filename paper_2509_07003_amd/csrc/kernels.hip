@@ -44,6 +44,19 @@
 #ifndef VESRNG_PIN_ARGUMENT_FETCH
 #define VESRNG_PIN_ARGUMENT_FETCH 1
 #endif
+// 0 (always, in the library): whole blocks of a ragged run leave as element-aligned vector stores.
+// 1 only in the measurement variant that first realigns them to 16-byte units across lanes (measured:
+// the extra instructions cost more than the aligned stores gain; the code is kept so that the
+// comparison can be repeated).
+#ifndef VESRNG_RAGGED_DPP_REALIGN
+#define VESRNG_RAGGED_DPP_REALIGN 0
+#endif
+// Measurement variants only: which operators may take the staging kernel.  -1 (the library): the
+// measured choice below; 0: none; 1: every operator, small tile only; 2: every operator, large tile
+// wherever the kernel has one.
+#ifndef VESRNG_TILING
+#define VESRNG_TILING -1
+#endif
 
 namespace vesrng {
 
@@ -512,6 +525,11 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
 }
 
 // ---- ragged / general kernels ----------------------------------------------------
+// The value the wave's first active lane holds, as a wave-uniform (scalar) value.
+__device__ __forceinline__ __attribute__((unused)) uint32_t first_lane(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(x)));
+}
+
 template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
@@ -538,6 +556,50 @@ ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* o
   // whole-block store into 12 + 4 bytes.
   asm volatile("" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
   const int64_t li0 = static_cast<int64_t>(s.li0);
+#if VESRNG_RAGGED_DPP_REALIGN
+  // A wave whose 64 blocks are whole and lie in ONE run holds 256 consecutive local elements that
+  // start m = li0 mod 4 elements past a 16-byte boundary.  Instead of 64 element-aligned stores the
+  // lanes realign: lane l assembles the aligned unit that starts inside its block from its own
+  // last m words and the first 4 - m words of lane l + 1's block (one DPP wave shift per word),
+  // lanes 0 .. 62 store aligned vectors, and the m + (4 - m) words at the wave's two ends leave
+  // word by word.  m is wave-uniform here, so the three shifts are scalar branches, not selects.
+  if constexpr (OP == kOpRaw || ((OP == kOpUniform || OP == kOpNormal) && DT == kF32)) {
+    const uint64_t run64 = static_cast<uint64_t>(run);
+    const uint32_t run_lo = static_cast<uint32_t>(run64), run_hi = static_cast<uint32_t>(run64 >> 32);
+    const bool same = (s.first == 0u && s.last == 4u) && run_lo == first_lane(run_lo) && run_hi == first_lane(run_hi);
+    if (__builtin_amdgcn_ballot_w64(same) == ~0ull) {
+      const uint32_t m = first_lane(static_cast<uint32_t>(li0) & 3u);
+      uint32_t* const dst = static_cast<uint32_t*>(out) + li0;
+      if (m == 0u) {
+        __builtin_nontemporal_store(u32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<u32x4*>(dst));
+        return;
+      }
+      const uint32_t lane = threadIdx.x & 63u;
+      // next[e]: word e of the block of lane l + 1 (lane 63 keeps its own: not used there).
+      uint32_t next[3];
+#pragma unroll
+      for (int e = 0; e < 3; ++e)
+        next[e] = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(v[e]), static_cast<int>(v[e]), 0x130,
+                                                                    0xF, 0xF, false));
+      u32x4 unit;
+      if (m == 1u) unit = u32x4{v[3], next[0], next[1], next[2]};
+      else if (m == 2u) unit = u32x4{v[2], v[3], next[0], next[1]};
+      else unit = u32x4{v[1], v[2], v[3], next[0]};
+      if (lane != 63u) __builtin_nontemporal_store(unit, reinterpret_cast<u32x4*>(dst + (4u - m)));
+      if (lane == 0u) {
+#pragma unroll
+        for (uint32_t e = 0; e < 3u; ++e)
+          if (e < 4u - m) dst[e] = v[e];
+      }
+      if (lane == 63u) {
+#pragma unroll
+        for (uint32_t e = 1; e < 4u; ++e)
+          if (e >= 4u - m) dst[e] = v[e];
+      }
+      return;
+    }
+  }
+#endif
   // Whole blocks of the fills leave as one store that is only element-aligned.
   if constexpr (OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) {
     if (s.first == 0u && s.last == 4u) {
@@ -726,24 +788,32 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 // through LDS doubles the rate of bf16 dropout (5.8 vs 2.4 TB/s) and helps the raw fill
 // (5.4 vs 4.3), the fp32 uniform fill (5.1 vs 4.2) and randint.  The 16-bit fills lose (3.0 vs
 // 3.5) and keep the ragged kernel.
+#if VESRNG_TILING == -1
 template <int OP, int DT>
 constexpr bool kTileable =
     (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP> || (OP == kOpUniform && DT == kF32));
-// The tiled kernel is bound by the latency of a workgroup's life, not by arithmetic or LDS, so
-// on LARGE shards the write-only fp32 fills gain from four units per thread (raw 5.4 -> 5.9,
-// uniform 5.1 -> 5.6, normal 4.2 (ragged kernel) -> 4.7 TB/s); on small shards the four times
-// fewer workgroups no longer fill the chip (a 22 MB normal fill: 9.0 vs 7.9 us).  Dropout and
-// randint, which issue more memory instructions per unit, lose (dropout fp32 6.25 -> 5.8,
-// randint 5.85 -> 5.1) and keep one unit.
+#else
 template <int OP, int DT>
-constexpr bool kBigTileable = ((OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) && UnitOf<OP, DT>::kElems == 4);
-// Smallest shard that takes the big tile (measured crossover: 2^24 elements, 2^26 for the normal fill).
+constexpr bool kTileable = (VESRNG_TILING != 0);
+#endif
+// Staged through LDS, the raw and fp32 uniform fills are bound by the latency of a workgroup's life,
+// not by arithmetic or LDS, so on LARGE shards they gain from four units per thread (measured on
+// column shards of 11 M to 358 M elements: raw 4.3-5.1 -> 5.0-5.75 TB/s, uniform 4.3-4.9 -> 4.7-5.5);
+// on small shards the four times fewer workgroups no longer fill the chip.  The fp32 normal fill
+// is bound by instruction issue instead and is fastest without staging at every size (5.0 TB/s
+// against 4.1 small tile / 4.8 large tile); dropout and randint, which issue more memory
+// instructions per unit, lose with the large tile and keep one unit.
+template <int OP, int DT>
+constexpr bool kBigTileable = (VESRNG_TILING == -1 || VESRNG_TILING == 2) &&
+                              ((OP == kOpRaw || OP == kOpUniform || (OP == kOpNormal && VESRNG_TILING == 2)) &&
+                               UnitOf<OP, DT>::kElems == 4);
+// Smallest shard that takes the big tile (measured crossover: between 5.6 M and 11 M elements).
 #ifdef VESRNG_BIG_TILE_MIN_ELEMS  // measurement variants only: force one tile size
 template <int OP>
 constexpr uint64_t kBigTileMinElems = VESRNG_BIG_TILE_MIN_ELEMS;
 #else
 template <int OP>
-constexpr uint64_t kBigTileMinElems = (OP == kOpNormal) ? (1ull << 26) : (1ull << 24);
+constexpr uint64_t kBigTileMinElems = 1ull << 23;
 #endif
 
 template <int OP, int DT, typename IT, int NOUT>

@@ -1,0 +1,68 @@
+"""The benchmark's issue model counts vector-ALU instructions per wavefront by class (bench.KERNEL_MIX).
+This test recounts them from a fresh compiler listing of the kernels (no GPU needed), so that the
+table cannot drift away from the code it describes."""
+import collections
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+
+@pytest.fixture(scope="module")
+def listing(tmp_path_factory):
+    from paper_2509_07003_amd import build
+    out = str(tmp_path_factory.mktemp("listing") / "kernels.s")
+    flags = [f for f in build.FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [build.HIPCC] + flags + ["-S", "--cuda-device-only", "-x", "hip", os.path.join(build.CSRC, "kernels.hip"), "-o", out]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    return open(out).read().split("\n")
+
+
+def histogram(listing, mangled_fragment):
+    """Mnemonic -> count over the body of the kernel whose mangled name contains the fragment."""
+    start = next(i for i, l in enumerate(listing) if l.startswith("_ZN") and mangled_fragment in l and ": " in l + " ")
+    counts = collections.Counter()
+    for l in listing[start + 1:]:
+        if l.startswith(".Lfunc_end"):
+            break
+        t = l.split(";")[0].strip()
+        if not t or t.startswith(".") or t.endswith(":"):
+            continue
+        counts[t.split()[0]] += 1
+    return counts
+
+
+def mangled(kernel):
+    """'aligned_kernel<2, 1, unsigned int, 1>' -> the Itanium fragment 'aligned_kernelILi2ELi1EjLi1EE'."""
+    name, args = re.match(r"(\w+)<(.*)>", kernel).groups()
+    enc = "".join("j" if a.strip() == "unsigned int" else "m" if a.strip() == "unsigned long" else "Li%sE" % a.strip()
+                  for a in args.split(","))
+    return "%sI%sE" % (name, enc)
+
+
+def test_instruction_mix_table_matches_the_compiler_listing(listing):
+    import bench
+    straight_line = {"aligned normal bf16", "aligned normal f32", "aligned dropout bf16"}
+    for tag, mix in bench.KERNEL_MIX.items():
+        h = histogram(listing, mangled(mix["kernel"]))
+        valu = sum(c for m, c in h.items() if m.startswith("v_"))
+        trans = sum(c for m, c in h.items() if re.match(r"v_(log|sqrt|sin|cos|exp|rcp|rsq)_f32", m))
+        assert h["v_mad_u64_u32"] == mix["mad_u64_u32"], tag
+        assert h["v_bitop3_b32"] == mix["bitop3_b32"], tag
+        assert trans == mix["trans"], tag
+        total = mix["mad_u64_u32"] + mix["bitop3_b32"] + mix["trans"] + mix["other"]
+        if tag in straight_line:
+            assert valu == total, (tag, valu, total)          # no branches: the listing is what a wave executes
+        else:
+            # Branchy kernels (a wave-uniform choice between two conversions; edge paths): a wave executes
+            # one side, so the table (the hardware counter's per-wave count) lies below the listing's total.
+            assert 0.7 * valu <= total <= valu, (tag, valu, total)
+    # The generator is 19 or more products (the first round's second product is by a zero counter word)
+    # and 20 three-way XORs per block; nothing else in it is a vector instruction.
+    h = histogram(listing, mangled("aligned_kernel<0, 0, unsigned int, 0>"))
+    assert h["v_mad_u64_u32"] >= 19 and h["v_bitop3_b32"] == 20 and h["v_xor_b32_e32"] == 0
