@@ -39,13 +39,13 @@ SETTLE_SECONDS = 0.25        # untimed launches before any timed region: the fir
 # tests/test_bench_model.py recounts them from a fresh listing.  "other" = everything that is
 # neither a Philox product (v_mad_u64_u32), a Philox XOR (v_bitop3_b32) nor a transcendental.
 KERNEL_MIX = {
-    "aligned normal bf16": {"kernel": "aligned_kernel<2, 1, unsigned int, 1>", "unit_elems": 8,
-                            "mad_u64_u32": 40, "bitop3_b32": 40, "trans": 16, "other": 65},
-    "aligned normal f32": {"kernel": "aligned_kernel<2, 0, unsigned int, 1>", "unit_elems": 4,
-                           "mad_u64_u32": 21, "bitop3_b32": 20, "trans": 8, "other": 39},
-    "aligned dropout bf16": {"kernel": "aligned_kernel<3, 1, unsigned int, 1>", "unit_elems": 8,
-                             "mad_u64_u32": 40, "bitop3_b32": 40, "trans": 0, "other": 76},
-    "aligned uniform f32": {"kernel": "aligned_kernel<1, 0, unsigned int, 0>", "unit_elems": 4,
+    "aligned normal bf16": {"kernel": "aligned_kernel<2, 1, unsigned int, 1, true>", "unit_elems": 8,
+                            "mad_u64_u32": 38, "bitop3_b32": 40, "trans": 16, "other": 56},
+    "aligned normal f32": {"kernel": "aligned_kernel<2, 0, unsigned int, 1, true>", "unit_elems": 4,
+                           "mad_u64_u32": 19, "bitop3_b32": 20, "trans": 8, "other": 30},
+    "aligned dropout bf16": {"kernel": "aligned_kernel<3, 1, unsigned int, 1, true>", "unit_elems": 8,
+                             "mad_u64_u32": 38, "bitop3_b32": 40, "trans": 0, "other": 67},
+    "aligned uniform f32": {"kernel": "aligned_kernel<1, 0, unsigned int, 0, false>", "unit_elems": 4,
                             "mad_u64_u32": 19, "bitop3_b32": 20, "trans": 0, "other": 24},
     "ragged normal f32": {"kernel": "ragged_kernel<2, 0, unsigned int, 1>", "unit_elems": 4,
                           "mad_u64_u32": 22, "bitop3_b32": 20, "trans": 8, "other": 50},
@@ -396,16 +396,21 @@ def design_choices(v, B, W, torch, once=False):
            ("nt", lambda: probe(B.PROBE_STORE_NT, units, None, a), nbytes),
            ("plain", lambda: probe(B.PROBE_STORE_PLAIN, units, None, a), nbytes),
            ("nt, element-aligned addresses", lambda: probe(B.PROBE_STORE_UNALIGNED, units, None, a), nbytes)])
-    entry("store cache-control bits (dropout traffic pattern)", "sc1 nt on both stores",
-          [("sc1 nt (kept)", lambda: probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
-           ("nt", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_NT, units, a, b, m), 2.5 * nbytes)])
+    entry("dropout traffic pattern: store bits, load bits, mask store width",
+          "non-temporal loads, sc1 nt stores, 8 mask bytes per thread",
+          [("nt loads, sc1 nt stores, 8-byte mask stores (kept)", lambda: probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
+           ("nt stores", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_NT, units, a, b, m), 2.5 * nbytes),
+           ("ordinary loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN, units, a, b, m), 2.5 * nbytes),
+           ("sc1 nt loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_SC1, units, a, b, m), 2.5 * nbytes),
+           ("sc0 sc1 loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1, units, a, b, m), 2.5 * nbytes),
+           ("two units per thread, 16-byte mask stores", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_WIDE_MASK, units, a, b, m), 2.5 * nbytes)])
     blocks = 1 << 30
     entry("three-way XOR of the generator (generator only)", "v_bitop3_b32",
           [("v_bitop3_b32 (kept)", lambda: probe(B.PROBE_PHILOX, blocks, None, a), blocks * 16),
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "ragged", "realign", "smalltile", "bigtile")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -429,9 +434,15 @@ def design_choices(v, B, W, torch, once=False):
     n3 = v.vesrng_local_shape(sh3)[1]
     ob = torch.empty(n3, dtype=torch.bfloat16, device="cuda")
     nrm = lambda L: (lambda: L.vesrng_normal(sh3, v.BF16, 0.0, 0.02, 3, 0, ob))
-    entry("C3 x64 bf16 normal fill: three-way XOR", "v_bitop3_b32",
-          [("library (kept)", nrm(v), 2 * n3), ("two v_xor_b32", nrm(variants["twoxor"]), 2 * n3)])
+    entry("C3 x64 bf16 normal fill: three-way XOR, run arithmetic", "v_bitop3_b32; run arithmetic once per wave in scalar registers",
+          [("library (kept)", nrm(v), 2 * n3), ("two v_xor_b32", nrm(variants["twoxor"]), 2 * n3),
+           ("run arithmetic per lane", nrm(variants["lanerun"]), 2 * n3)])
     del ob
+    of3 = torch.empty(n3, dtype=torch.float32, device="cuda")
+    nrm32 = lambda L: (lambda: L.vesrng_normal(sh3, v.F32, 0.0, 0.02, 3, 0, of3))
+    entry("fp32 normal fill on C3 x64's shard: run arithmetic", "once per wave in scalar registers",
+          [("library (kept)", nrm32(v), 4 * n3), ("run arithmetic per lane", nrm32(variants["lanerun"]), 4 * n3)])
+    del of3
     # The pinning is about the latency of a workgroup's life: it shows on the small configs (GPU-side time per
     # launch, replayed from a HIP graph), not on shards that keep the chip busy for hundreds of microseconds.
     for wl, copies in ((W.C1, 256), (W.C3, 32), (W.C4, 8)):
@@ -533,7 +544,7 @@ def main():
     value = nbytes / (wall / a.steps) / 1e9
     avg_ms = e0.elapsed_time(e1) / a.steps
     achieved = nbytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "vesrng::aligned_kernel<3 (dropout), 1 (bf16), unsigned int, 1 run axis>",
+    roofline = {"bound": "hbm", "kernel": "vesrng::aligned_kernel<3 (dropout), 1 (bf16), unsigned int, 1 run axis, runs of whole waves>",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": read_traffic("c5_dropout_bf16"), "avg_launch_ms": avg_ms,
                 "timing": "HIP events on the launch stream around the %d launches of the timed region, elapsed / %d "

@@ -40,7 +40,13 @@ typedef enum {
                                           (out + 4 bytes): what a ragged run's whole blocks look like */
   VESRNG_PROBE_DROPOUT_TRAFFIC_NT = 8, /* the traffic pattern with plain non-temporal stores */
   VESRNG_PROBE_PHILOX_TWO_XOR = 9,     /* the generator written as a ^ b ^ c (two v_xor_b32) */
-  VESRNG_PROBE_STORE_4_PER_THREAD = 10 /* sc1 nt stores, four consecutive units per thread */
+  VESRNG_PROBE_STORE_4_PER_THREAD = 10, /* sc1 nt stores, four consecutive units per thread */
+  /* Alternatives of the dropout traffic pattern (all with sc1 nt stores): */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_WIDE_MASK = 11,  /* two units per thread (a wave covers two contiguous KiB), the 16 mask
+                                                   bytes of the pair leave as ONE 16-byte store per thread */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN = 12, /* ordinary loads instead of non-temporal ones */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC1 = 13,   /* loads with the cache-control bits sc1 nt */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1 = 14 /* loads with sc0 sc1 (system scope) */
 } vesrng_probe_kind;
 
 VESRNG_API vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t units, const void* in, void* out,

@@ -40,6 +40,9 @@ TARGETS = {
     # Three-way XORs of the generator as two v_xor_b32.
     "variant_twoxor": {"lib": "libvesrng_variant_twoxor.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=twoxor", "VESRNG_PHILOX_BITOP3=0"]},
+    # Aligned kernels with the run arithmetic per lane even where runs are whole wavefronts long.
+    "variant_lanerun": {"lib": "libvesrng_variant_lanerun.so", "sources": PRODUCT_SOURCES,
+                        "defines": ["VESRNG_VARIANT_TAG=lanerun", "VESRNG_WAVE_UNIFORM_RUNS=0"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

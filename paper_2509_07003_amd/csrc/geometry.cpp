@@ -347,6 +347,7 @@ PlanT<IT> make_plan(const Geometry& g, const RunShape& rs, uint64_t offset, uint
   p.units_per_run = static_cast<IT>(units_per_run);
   p.units_div = DivOf<IT>::make(units_per_run);
   p.n_outer = static_cast<int32_t>(rs.outer.size());
+  p.wave_runs = (units_per_run % 64 == 0) ? 1 : 0;
   for (size_t k = 0; k < rs.outer.size(); ++k) {
     p.outer_extent[k] = static_cast<IT>(rs.outer[k].extent);
     p.outer_div[k] = DivOf<IT>::make(static_cast<uint64_t>(rs.outer[k].extent));

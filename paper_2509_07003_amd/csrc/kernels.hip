@@ -51,6 +51,11 @@
 #ifndef VESRNG_RAGGED_DPP_REALIGN
 #define VESRNG_RAGGED_DPP_REALIGN 0
 #endif
+// 1 (always, in the library): shards whose runs are whole wavefronts long take the aligned kernel's form
+// with the run arithmetic in scalar registers.  0 only in the measurement variant that times the per-lane form.
+#ifndef VESRNG_WAVE_UNIFORM_RUNS
+#define VESRNG_WAVE_UNIFORM_RUNS 1
+#endif
 // Measurement variants only: which operators may take the staging kernel.  -1 (the library): the
 // measured choice below; 0: none; 1: every operator, small tile only; 2: every operator, large tile
 // wherever the kernel has one.
@@ -345,36 +350,60 @@ __device__ __forceinline__ BlockSpan<IT> block_span(const PlanT<IT>& plan, IT ru
 }
 
 // ---- aligned kernels -----------------------------------------------------------
-template <int OP, int DT, typename IT, int NOUT>
+// The value the wave's first active lane holds, as a wave-uniform (scalar) value.
+__device__ __forceinline__ __attribute__((unused)) uint32_t first_lane(uint32_t x) {
+  return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(x)));
+}
+
+// WAVE: every run is a whole number of wavefronts long (units_per_run is a multiple of 64), so the 64
+// units of a wave lie in ONE run: the run's number, its stream position and the 64-bit stride products
+// are the same for all lanes and are worked out once per wave in scalar registers; a lane only adds
+// its slot.  (All of it costs vector-ALU issue slots otherwise, and the 16-bit fills and the normal
+// fills are bound by exactly those.)
+template <int OP, int DT, typename IT, int NOUT, bool WAVE>
 __global__ void __launch_bounds__(kThreads)
 aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
   constexpr int NB = UnitOf<OP, DT>::kBlocks;
   constexpr int V = UnitOf<OP, DT>::kElems;
+  static_assert(!(WAVE && NOUT == 0), "a single run needs no run arithmetic at all");
   // Threads past the end compute unit 0 again and skip the stores: no early exit, so all
   // kernel arguments are fetched in one batch at the top.
   touch_params<OP>(prm);
 #if VESRNG_PIN_ARGUMENT_FETCH
   asm volatile("" ::"s"(out), "s"(mask));
 #endif
-  uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   // randint writes 32 bytes per generator block.  Lane by lane that would be two stores of 16
   // bytes at a 32-byte stride, which run at a third of the contiguous rate.  Instead the lane
   // pair (2k, 2k+1) of a wave computes blocks k and 32 + k of the wave's 64 and the two trade
   // halves, so that either store instruction writes 1 KiB without gaps.
   const uint32_t lane = threadIdx.x & 63u;
-  const uint64_t wave_base = t64 - lane;
-  if constexpr (OP == kOpRandint) t64 = wave_base + (lane >> 1) + ((lane & 1u) << 5);
-  const bool live = t64 < plan.total_units;
+  const uint32_t slot = (OP == kOpRandint) ? (lane >> 1) + ((lane & 1u) << 5) : lane;  // the wave's unit this lane takes
+  uint64_t wave_base, w64, block0;
+  bool live;
+  if constexpr (WAVE) {
+    wave_base = static_cast<uint64_t>(blockIdx.x) * kThreads + (first_lane(threadIdx.x >> 6) << 6);  // scalar
+    live = wave_base < plan.total_units;  // total_units is a multiple of 64 here: the whole wave or none of it
+    const uint64_t base = live ? wave_base : 0;
+    const IT run = plan.units_div.div(static_cast<IT>(base));
+    const IT unit0 = static_cast<IT>(base) - run * plan.units_per_run;
+    const uint64_t start = run_position<NOUT>(plan, run) + static_cast<uint64_t>(unit0) * V;  // of the wave's first unit
+    block0 = (start >> 2) + slot * static_cast<uint32_t>(V / 4);
+    w64 = base + slot;
+  } else {
+    const uint64_t t0 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    wave_base = t0 - lane;
+    const uint64_t t64 = wave_base + slot;
+    live = t64 < plan.total_units;
 #if !VESRNG_PIN_ARGUMENT_FETCH
-  if constexpr (OP != kOpRandint)
-    if (!live) return;  // measurement variant: the plain early exit
+    if constexpr (OP != kOpRandint)
+      if (!live) return;  // measurement variant: the plain early exit
 #endif
-  const uint64_t w64 = live ? t64 : 0;
-  const IT w = static_cast<IT>(w64);
-  IT run, unit;
-  uint64_t run_pos;
-  locate<NOUT>(plan, w, run, unit, run_pos);
-  const uint64_t block0 = (run_pos + static_cast<uint64_t>(unit) * V) >> 2;
+    w64 = live ? t64 : 0;
+    IT run, unit;
+    uint64_t run_pos;
+    locate<NOUT>(plan, static_cast<IT>(w64), run, unit, run_pos);
+    block0 = (run_pos + static_cast<uint64_t>(unit) * V) >> 2;
+  }
 
   // A shard that is ONE run (contiguous in the global tensor) may end inside a unit: its last
   // unit is then written element by element, and its 16-byte load would pass the end of x.
@@ -525,11 +554,6 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
 }
 
 // ---- ragged / general kernels ----------------------------------------------------
-// The value the wave's first active lane holds, as a wave-uniform (scalar) value.
-__device__ __forceinline__ __attribute__((unused)) uint32_t first_lane(uint32_t x) {
-  return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(x)));
-}
-
 template <int OP, int DT, typename IT, int NOUT>
 __global__ void __launch_bounds__(kThreads)
 ragged_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* out, uint8_t* mask) {
@@ -830,7 +854,10 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
   switch (flavour) {
     case kAligned:
-      return enqueue(aligned_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);
+      if constexpr (NOUT != 0 && VESRNG_WAVE_UNIFORM_RUNS != 0)
+        if (plan.wave_runs)
+          return enqueue(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, stream, plan, prm, x, out, mask);
+      return enqueue(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
       if constexpr (kTileable<OP, DT>)
         return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1>, grid, block, stream, plan, prm,

@@ -74,6 +74,8 @@ struct PlanT {
   IT units_per_run;     // work units one run is cut into
   Div units_div;        // divides by units_per_run
   int32_t n_outer;      // axes that enumerate runs; axis 0 varies fastest
+  int32_t wave_runs;    // units_per_run is a multiple of 64: the 64 units of a wavefront lie in ONE run, so the
+                        // run's number, position and strides can be worked out once per wave in scalar registers
   IT outer_extent[kMaxOuter];
   Div outer_div[kMaxOuter];
   uint64_t outer_stride[kMaxOuter]; // global stride of the axis, in elements

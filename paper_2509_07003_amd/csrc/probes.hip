@@ -92,6 +92,46 @@ dropout_traffic_probe(const u32x4* in, u32x4* out, u32x2* mask, uint64_t units) 
   store8<FORM>(m, mask + t);
 }
 
+// Variants of the traffic pattern.  LOAD: 0 = non-temporal builtin, 1 = ordinary, 2 = sc1 nt, 3 = sc0 sc1.
+template <int LOAD>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+  if constexpr (LOAD == 0) return __builtin_nontemporal_load(p);
+  else if constexpr (LOAD == 1) return *p;
+  else {
+    u32x4 v;
+    // The compiler does not count this load: the wait for its data is written out.
+    if constexpr (LOAD == 2) asm volatile("global_load_dwordx4 %0, %1, off sc1 nt\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    else asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return v;
+  }
+}
+template <int LOAD>
+__global__ void __launch_bounds__(kThreads)
+dropout_traffic_load_probe(const u32x4* in, u32x4* out, u32x2* mask, uint64_t units) {
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (t >= units) return;
+  const u32x4 v = load16<LOAD>(in + t);
+  const u32x2 m = {v[0] & 0x01010101u, v[1] & 0x01010101u};
+  vesrng::stream_store(v, out + t);
+  vesrng::stream_store(m, mask + t);
+}
+
+// Two units per thread: a wave covers 2 KiB of x and y as two contiguous KiB (units base + lane and
+// base + 64 + lane) and writes its 1 KiB of mask bytes with ONE 16-byte store per lane.  Only the traffic
+// pattern is of interest: the mask bytes written are not the ones of the lane's own units.
+__global__ void __launch_bounds__(kThreads)
+dropout_traffic_wide_mask_probe(const u32x4* in, u32x4* out, u32x4* mask, uint64_t units) {
+  const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint64_t u0 = 2 * (t - lane) + lane, u1 = u0 + 64;
+  if (u1 >= units) return;
+  const u32x4 a = __builtin_nontemporal_load(in + u0), b = __builtin_nontemporal_load(in + u1);
+  const u32x4 m = {a[0] & 0x01010101u, a[1] & 0x01010101u, b[0] & 0x01010101u, b[1] & 0x01010101u};
+  vesrng::stream_store(a, out + u0);
+  vesrng::stream_store(b, out + u1);
+  vesrng::stream_store(m, mask + t);
+}
+
 // Philox4x32-10 blocks and nothing else (the results are folded and, in practice, never stored).
 template <bool BITOP3>
 __global__ void __launch_bounds__(kThreads) philox_probe(uint32_t* out, uint64_t blocks, uint32_t k0, uint32_t k1) {
@@ -254,6 +294,22 @@ extern "C" vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t uni
       else
         hipLaunchKernelGGL(dropout_traffic_probe<kNonTemporal>, grid, block, 0, stream, i, o, static_cast<u32x2*>(out2),
                            units);
+      break;
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_WIDE_MASK:
+      if (!in || !out2) return VESRNG_ERR_NULL;
+      hipLaunchKernelGGL(dropout_traffic_wide_mask_probe, dim3(static_cast<uint32_t>((blocks + 1) / 2)), block, 0, stream, i,
+                         o, static_cast<u32x4*>(out2), units);
+      break;
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN:
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC1:
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1:
+      if (!in || !out2) return VESRNG_ERR_NULL;
+      if (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN)
+        hipLaunchKernelGGL(dropout_traffic_load_probe<1>, grid, block, 0, stream, i, o, static_cast<u32x2*>(out2), units);
+      else if (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC1)
+        hipLaunchKernelGGL(dropout_traffic_load_probe<2>, grid, block, 0, stream, i, o, static_cast<u32x2*>(out2), units);
+      else
+        hipLaunchKernelGGL(dropout_traffic_load_probe<3>, grid, block, 0, stream, i, o, static_cast<u32x2*>(out2), units);
       break;
     case VESRNG_PROBE_PHILOX:
       // A grid-stride loop over `units` generator blocks on 16 workgroups per compute unit.

@@ -38,10 +38,10 @@ def histogram(listing, mangled_fragment):
 
 
 def mangled(kernel):
-    """'aligned_kernel<2, 1, unsigned int, 1>' -> the Itanium fragment 'aligned_kernelILi2ELi1EjLi1EE'."""
+    """'aligned_kernel<2, 1, unsigned int, 1, true>' -> the Itanium fragment 'aligned_kernelILi2ELi1EjLi1ELb1EE'."""
     name, args = re.match(r"(\w+)<(.*)>", kernel).groups()
-    enc = "".join("j" if a.strip() == "unsigned int" else "m" if a.strip() == "unsigned long" else "Li%sE" % a.strip()
-                  for a in args.split(","))
+    code = {"unsigned int": "j", "unsigned long": "m", "true": "Lb1E", "false": "Lb0E"}
+    enc = "".join(code.get(a.strip(), "Li%sE" % a.strip()) for a in args.split(","))
     return "%sI%sE" % (name, enc)
 
 
@@ -64,5 +64,24 @@ def test_instruction_mix_table_matches_the_compiler_listing(listing):
             assert 0.7 * valu <= total <= valu, (tag, valu, total)
     # The generator is 19 or more products (the first round's second product is by a zero counter word)
     # and 20 three-way XORs per block; nothing else in it is a vector instruction.
-    h = histogram(listing, mangled("aligned_kernel<0, 0, unsigned int, 0>"))
+    h = histogram(listing, mangled("aligned_kernel<0, 0, unsigned int, 0, false>"))
     assert h["v_mad_u64_u32"] >= 19 and h["v_bitop3_b32"] == 20 and h["v_xor_b32_e32"] == 0
+
+
+def test_instruction_mix_table_matches_the_committed_counter_profile():
+    """The per-wave totals of bench.KERNEL_MIX are what the hardware counters read (SQ_INSTS_VALU / SQ_WAVES in
+    profiles/counters_bench_kernels.txt, written from a rocprofv3 --pmc run of bench.py --counters-pass)."""
+    import bench
+    text = open(os.path.join(ROOT, "profiles", "counters_bench_kernels.txt")).read()
+    line = next(l for l in text.splitlines() if l.startswith("valu_per_wave:"))
+    measured = {}
+    for item in line.split(":", 1)[1].split(";"):
+        name, value = item.rsplit("=", 1)
+        measured.setdefault(name.split("@")[0].strip(), []).append(float(value))
+    seen = 0
+    for tag, mix in bench.KERNEL_MIX.items():
+        total = mix["mad_u64_u32"] + mix["bitop3_b32"] + mix["trans"] + mix["other"]
+        for value in measured.get(mix["kernel"], []):
+            assert abs(value - total) <= 1.0, (tag, value, total)
+            seen += 1
+    assert seen >= 5

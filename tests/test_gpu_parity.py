@@ -745,13 +745,22 @@ def test_ceiling_probes_do_what_they_say():
     a = a[:units * 4].clone()
     bb = torch.zeros_like(a)
     b.vesrng_bench_probe(b.PROBE_COPY, units, a, bb)
-    for kind in (b.PROBE_DROPOUT_TRAFFIC, b.PROBE_DROPOUT_TRAFFIC_NT):
+    for kind in (b.PROBE_DROPOUT_TRAFFIC, b.PROBE_DROPOUT_TRAFFIC_NT, b.PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN,
+                 b.PROBE_DROPOUT_TRAFFIC_LOAD_SC1, b.PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1):
         m = torch.zeros(units * 2, dtype=torch.int32, device=DEV)
         c = torch.zeros_like(a)
         b.vesrng_bench_probe(kind, units, a, c, m)
         torch.cuda.synchronize()
         assert torch.equal(a, c)
         assert np.array_equal(m.cpu().numpy().reshape(units, 2), want[:, :2] & 0x01010101)
+    # Wide-mask form: x and y as in the others (whole waves of unit pairs only), 16 mask bytes per thread.
+    wu = 1024
+    aw = a[:wu * 4].clone()
+    c = torch.zeros_like(aw)
+    m = torch.zeros(wu * 2, dtype=torch.int32, device=DEV)
+    b.vesrng_bench_probe(b.PROBE_DROPOUT_TRAFFIC_WIDE_MASK, wu, aw, c, m)
+    torch.cuda.synchronize()
+    assert torch.equal(aw, c) and m.cpu().numpy().any()
     # Generator-only and issue-rate loops generate and discard: bb must stay a copy of a.
     b.vesrng_bench_probe(b.PROBE_PHILOX, 1 << 20, None, bb)
     b.vesrng_bench_probe(b.PROBE_PHILOX_TWO_XOR, 1 << 20, None, bb)
