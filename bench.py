@@ -410,7 +410,7 @@ def design_choices(v, B, W, torch, once=False):
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -472,7 +472,8 @@ def design_choices(v, B, W, torch, once=False):
                    ("no staging, element-aligned stores", call(variants["ragged"]), 4 * nr),
                    ("no staging, realigned across lanes (DPP)", call(variants["realign"]), 4 * nr),
                    ("staged, small tile", call(variants["smalltile"]), 4 * nr),
-                   ("staged, large tile", call(variants["bigtile"]), 4 * nr)])
+                   ("staged, large tile", call(variants["bigtile"]), 4 * nr),
+                   ("library's choice with the tile map per wavefront (scalar)", call(variants["wavetile"]), 4 * nr)])
     return res
 
 

@@ -43,6 +43,9 @@ TARGETS = {
     # Aligned kernels with the run arithmetic per lane even where runs are whole wavefronts long.
     "variant_lanerun": {"lib": "libvesrng_variant_lanerun.so", "sources": PRODUCT_SOURCES,
                         "defines": ["VESRNG_VARIANT_TAG=lanerun", "VESRNG_WAVE_UNIFORM_RUNS=0"]},
+    # The staging kernel with its tile map worked out once per wavefront in scalar registers (runs of 64 blocks and more).
+    "variant_wavetile": {"lib": "libvesrng_variant_wavetile.so", "sources": PRODUCT_SOURCES,
+                         "defines": ["VESRNG_VARIANT_TAG=wavetile", "VESRNG_TILE_WAVE_MAP=1"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},
@@ -106,7 +109,7 @@ def build(target: str = "vesrng", verbose: bool = False) -> str:
     return lib
 
 
-def build_all(verbose: bool = False, jobs: int = 4):
+def build_all(verbose: bool = False, jobs: int = min(8, os.cpu_count() or 1)):
     """Compiles every target, a few at a time (each hipcc run is single-threaded)."""
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         return list(pool.map(lambda name: build(name, verbose), TARGETS))

@@ -56,6 +56,12 @@
 #ifndef VESRNG_WAVE_UNIFORM_RUNS
 #define VESRNG_WAVE_UNIFORM_RUNS 1
 #endif
+// 0 (always, in the library): the staging kernel works its tile map out per lane.  1 only in the measurement
+// variant that works it out once per wavefront in scalar registers where runs are long enough (measured: slower -
+// the scalar unit, one per compute unit, then issues more instructions per wave than the vector ALUs save).
+#ifndef VESRNG_TILE_WAVE_MAP
+#define VESRNG_TILE_WAVE_MAP 0
+#endif
 // Measurement variants only: which operators may take the staging kernel.  -1 (the library): the
 // measured choice below; 0: none; 1: every operator, small tile only; 2: every operator, large tile
 // wherever the kernel has one.
@@ -472,8 +478,9 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 
 // ---- tiled kernels ---------------------------------------------------------------
 // UPT: aligned units a thread takes out of the tile in stage B (the tile is up to kThreads * UPT
-// units).
-template <int OP, int DT, typename IT, int NOUT, int UPT>
+// units).  WAVE (measurement variant only): runs have at least 64 blocks and stage A works the tile map out
+// once per wavefront in scalar registers (plan.h: tile_wave) instead of once per lane.
+template <int OP, int DT, typename IT, int NOUT, int UPT, bool WAVE>
 __global__ void __launch_bounds__(kThreads)
 tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, const void* xin, void* out,
              uint8_t* mask) {
@@ -494,7 +501,16 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
 
   // Stage A: one block per thread (one pass for 4-byte units, two for bfloat16 units).
   for (IT k = threadIdx.x; k < count; k += kThreads) {
-    const TileSpot spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
+    TileSpot spot;
+    if constexpr (WAVE) {
+      // Lane 0 of the wave holds the wave's first block number (lanes run out at the top end only).
+      const uint64_t k64 = static_cast<uint64_t>(k);
+      const uint64_t kw = (static_cast<uint64_t>(first_lane(static_cast<uint32_t>(k64 >> 32))) << 32) |
+                          first_lane(static_cast<uint32_t>(k64));
+      spot = tile_spot_of_lane(tile_wave<NOUT>(plan, i0, lim, static_cast<IT>(wa + static_cast<IT>(kw))), threadIdx.x & 63u);
+    } else {
+      spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
+    }
     uint32_t d[4], v[4];
     philox_block(spot.block, prm.key0, prm.key1, d);
     convert_block<OP, DT>(d, prm, v);
@@ -859,16 +875,24 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
           return enqueue(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, stream, plan, prm, x, out, mask);
       return enqueue(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
-      if constexpr (kTileable<OP, DT>)
-        return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1>, grid, block, stream, plan, prm,
-                       TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
-                       mask);
+      if constexpr (kTileable<OP, DT>) {
+        const TileArgs<IT> ta{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel};
+        if constexpr (VESRNG_TILE_WAVE_MAP != 0)
+          if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
+            return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1, true>, grid, block, stream, plan, prm, ta, x, out, mask);
+        return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1, false>, grid, block, stream, plan, prm, ta, x, out, mask);
+      }
       break;
     case kTiledBig:
-      if constexpr (kBigTileable<OP, DT>)
-        return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits>, grid, block, stream, plan, prm,
-                       TileArgs<IT>{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel}, x, out,
+      if constexpr (kBigTileable<OP, DT>) {
+        const TileArgs<IT> ta{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel};
+        if constexpr (VESRNG_TILE_WAVE_MAP != 0)
+          if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
+            return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits, true>, grid, block, stream, plan, prm, ta, x, out,
+                           mask);
+        return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits, false>, grid, block, stream, plan, prm, ta, x, out,
                        mask);
+      }
       break;
     case kRagged:
       return enqueue(ragged_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);

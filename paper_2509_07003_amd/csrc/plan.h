@@ -143,6 +143,8 @@ struct TileArgs {
   IT tile_units;                        // aligned units of the local tensor per tile
   uint64_t local_numel;
 };
+// A run of at least 64 blocks lets stage A work out the tile map once per wavefront (tile_wave).
+constexpr uint64_t kTileWaveMinBlocks = 64;
 
 // Flattened number of the generator block that holds local element i.
 template <int NOUT, typename IT>
@@ -177,6 +179,53 @@ VESRNG_HD TileSpot tile_spot(const PlanT<IT>& plan, uint64_t i0, int32_t lim, IT
   s.rel = static_cast<int32_t>(run_lo + static_cast<ST>(4 * bi) - static_cast<ST>(static_cast<uint32_t>(run_pos) & 3u));
   s.lo = static_cast<int32_t>(run_lo > zero ? (run_lo < top ? run_lo : top) : zero);
   s.hi = static_cast<int32_t>(run_hi < top ? (run_hi > zero ? run_hi : zero) : top);
+  return s;
+}
+
+// The same map worked out once per WAVEFRONT.  In stage A the 64 lanes of a wave take 64 consecutive
+// flattened block numbers wf .. wf + 63.  When a run has at least 64 blocks these lie in at most two runs:
+// `split` lanes in the run of block wf, the rest at the start of the next run.  Everything that depends on
+// the run - its stream position, its bounds clamped to the tile, the division that finds it - is the same
+// for all lanes of a part and is computed here from wave-uniform values (on the GPU: in scalar registers);
+// a lane then only selects its part and adds its offset (tile_spot_of_lane).  rel_a / rel_b are the tile
+// positions of the FIRST block of each part, which lie within a block of the tile, so they fit 32 bits
+// whatever the run length.
+struct TileWave {
+  uint64_t block_a, block_b;  // generator block of lane 0 / of lane `split`
+  uint32_t split;             // lanes below belong to part a (>= 64: the whole wave)
+  int32_t rel_a, lo_a, hi_a, rel_b, lo_b, hi_b;
+};
+template <int NOUT, typename IT>
+VESRNG_HD TileWave tile_wave(const PlanT<IT>& plan, uint64_t i0, int32_t lim, IT wf) {
+  using ST = typename SignedOf<IT>::type;
+  const ST zero = 0, top = static_cast<ST>(lim);
+  IT run, bi;
+  uint64_t pos_a;
+  locate<NOUT>(plan, wf, run, bi, pos_a);
+  const uint64_t pos_b = run_position<NOUT>(plan, static_cast<IT>(run + 1));
+  const IT left = plan.units_per_run - bi;  // blocks of this run from bi on
+  TileWave t;
+  t.split = left < 64 ? static_cast<uint32_t>(left) : 64u;
+  const ST lo_a = static_cast<ST>(run * plan.run_len) - static_cast<ST>(i0), hi_a = lo_a + static_cast<ST>(plan.run_len);
+  const ST lo_b = hi_a, hi_b = hi_a + static_cast<ST>(plan.run_len);  // the local tensor is run after run
+  t.block_a = (pos_a >> 2) + bi;
+  t.block_b = pos_b >> 2;
+  t.rel_a = static_cast<int32_t>(lo_a + static_cast<ST>(4 * bi) - static_cast<ST>(static_cast<uint32_t>(pos_a) & 3u));
+  t.rel_b = static_cast<int32_t>(lo_b - static_cast<ST>(static_cast<uint32_t>(pos_b) & 3u));
+  t.lo_a = static_cast<int32_t>(lo_a > zero ? (lo_a < top ? lo_a : top) : zero);
+  t.hi_a = static_cast<int32_t>(hi_a < top ? (hi_a > zero ? hi_a : zero) : top);
+  t.lo_b = static_cast<int32_t>(lo_b > zero ? (lo_b < top ? lo_b : top) : zero);
+  t.hi_b = static_cast<int32_t>(hi_b < top ? (hi_b > zero ? hi_b : zero) : top);
+  return t;
+}
+VESRNG_HD TileSpot tile_spot_of_lane(const TileWave& t, uint32_t lane) {
+  const bool b = lane >= t.split;
+  const uint32_t off = b ? lane - t.split : lane;
+  TileSpot s;
+  s.block = (b ? t.block_b : t.block_a) + off;
+  s.rel = (b ? t.rel_b : t.rel_a) + static_cast<int32_t>(4u * off);
+  s.lo = b ? t.lo_b : t.lo_a;
+  s.hi = b ? t.hi_b : t.hi_a;
   return s;
 }
 

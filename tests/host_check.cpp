@@ -110,8 +110,22 @@ void emulate_tile(const PlanT<IT>& plan, const TileArgs<IT>& ta, uint64_t unit_e
   const IT count = tile_block_of<NOUT>(plan, ta, i1 - 1) - wa + 1;
   std::vector<long long> slot(static_cast<size_t>(lim), -1);
   long long dummy = 0;
+  // The per-wavefront form of the map (64 consecutive block numbers share one tile_wave; used by a measurement
+  // variant of the kernel where runs have at least 64 blocks) is walked next to the per-lane form the library
+  // uses: where both exist they must agree field by field.
+  const bool wave = static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks;
+  TileWave tw{};
   for (IT k = 0; k < count; ++k) {
-    const TileSpot spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
+    TileSpot spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
+    if (wave) {
+      if (k % 64 == 0) tw = tile_wave<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
+      const TileSpot ws = tile_spot_of_lane(tw, static_cast<uint32_t>(k % 64));
+      // Dead slots beyond a run's last block may differ in where they point, never in being outside [lo, hi).
+      const bool live_a = spot.rel + 4 > spot.lo && spot.rel < spot.hi, live_b = ws.rel + 4 > ws.lo && ws.rel < ws.hi;
+      if (live_a != live_b || (live_a && (ws.block != spot.block || ws.rel != spot.rel || ws.lo != spot.lo || ws.hi != spot.hi)))
+        std::printf(" | OUT-OF-TILE wave-map-mismatch-at-block-%llu", static_cast<unsigned long long>(k));
+      spot = ws;
+    }
     // The kernel's own choice between the interior path and the edge path.
     const int32_t rel = spot.rel, lo = spot.lo, hi = spot.hi;
     for (int e = 0; e < 4; ++e) {

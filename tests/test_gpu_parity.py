@@ -934,7 +934,8 @@ def test_table5_large_tensors_on_sampled_windows(label, shape):
     cases = [([2, 4], [("S", 1), ("S", 1)], [1, 2]),               # "#1 and #1": nested, same dimension
              ([8], [("IS", 1, 4)], [5]),                           # interleaved: heads dealt out in 4 groups
              ([3], [("S", 4)], [1]),                               # ragged innermost dimension (64 or 128 over 3)
-             ([3, 3], [("S", 3), ("S", 4)], [2, 2])]               # "#3 and #4", both ragged
+             ([3, 3], [("S", 3), ("S", 4)], [2, 2]),               # "#3 and #4", both ragged
+             ([2], [("S", 1)], [1])]                               # "#1": aligned runs; 2^31 local elements at 16 GB (64-bit index kernels)
     for mesh, pls, coord in cases:
         args = (shape, mesh, pls, coord)
         sh = v.Sharding(*args)
