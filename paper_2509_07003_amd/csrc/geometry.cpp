@@ -330,8 +330,10 @@ bool plan_theta(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t
   tp->group0 = first_step / 4;
   const uint64_t groups = last_step / 4 - tp->group0 + 1;
   tp->total_threads = groups * tp->cols;
-  tp->narrow = (tp->total_threads < (1ull << 31) && tp->cols < (1ull << 31)) ? 1u : 0u;
-  tp->cols_div = tp->narrow ? make_div32(static_cast<uint32_t>(tp->cols)) : Div32{1, 0, 0};
+  // Thread numbers are split into (group, column) with one 32-bit multiply-shift division; shards beyond that
+  // (2^35 fp32 elements and more) are left to the element-wise kernel.
+  if (tp->total_threads >= (1ull << 31) || tp->cols >= (1ull << 31)) return false;
+  tp->cols_div = make_div32(static_cast<uint32_t>(tp->cols));
   tp->origin = g.origin;
   tp->local_numel = n;
   tp->block0 = offset / 4;

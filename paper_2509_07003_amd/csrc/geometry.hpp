@@ -115,8 +115,7 @@ LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offse
 struct ThetaPlan {
   uint64_t theta = 0;          // Theta
   uint64_t cols = 0;           // Theta / unit_elems: threads per step group
-  Div32 cols_div{};            // divides by cols (when narrow)
-  uint32_t narrow = 0;         // thread numbers and cols are below 2^31: 32-bit division
+  Div32 cols_div{};            // divides by cols (thread numbers and cols are below 2^31)
   uint64_t group0 = 0;         // first step group that holds an element of the shard
   uint64_t origin = 0;         // global flat index of local element 0
   uint64_t local_numel = 0;

@@ -731,15 +731,8 @@ theta_kernel(const ThetaPlan tp, const OpParams prm, const void* xin, void* out,
   touch_params<OP>(prm);
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (t >= tp.total_threads) return;
-  uint64_t gi, c;
-  if (tp.narrow) {
-    const uint32_t q = tp.cols_div.div(static_cast<uint32_t>(t));
-    gi = q;
-    c = static_cast<uint32_t>(t) - q * static_cast<uint32_t>(tp.cols);
-  } else {
-    gi = t / tp.cols;
-    c = t - gi * tp.cols;
-  }
+  const uint32_t gi = tp.cols_div.div(static_cast<uint32_t>(t));
+  const uint64_t c = static_cast<uint32_t>(t) - gi * static_cast<uint32_t>(tp.cols);
   const uint64_t group = tp.group0 + gi;
   const uint64_t block = tp.block0 + group;      // the same for all V virtual threads
   const uint64_t tau0 = c * V;
