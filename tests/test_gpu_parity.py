@@ -647,6 +647,7 @@ def test_dropout_add_residual(dtype):
     seed, offset = 2024, 128
     code, ocode = (v.F32, oracle.F32) if dtype == "f32" else (v.BF16, oracle.BF16)
     for args in (([64, 4096], [4], [("S", 0)], [3]),                               # aligned
+                 ([8, 64, 1024], [2], [("S", 1)], [1]),                            # aligned, 8 runs of whole wavefronts
                  ([300, 333], [3], [("S", 1)], [1]),                               # ragged column shard (tiled)
                  ([40, 7], [2], [("S", 1)], [1]),                                  # runs of 3: element-wise
                  ([96], [2, 3], [("IS", 0, 2), ("S", 0)], [1, 1])):                # not a box
@@ -979,6 +980,7 @@ def test_table5_large_tensors_on_sampled_windows(label, shape):
 
 # ------------------------------------------------------------- binary16 -------
 F16_CASES = [([64, 4096], [4], [("S", 0)], [3]),                                 # aligned
+             ([6, 64, 512], [2, 2], [("S", 1), ("S", 0)], [1, 1]),               # aligned, several runs of whole wavefronts
              ([300, 333], [3], [("S", 1)], [1]),                                 # ragged column shard (tiled for dropout)
              ([40, 7], [2], [("S", 1)], [1]),                                    # runs of 3: element-wise edges only
              ([5, 6, 7, 8, 9], [2, 2], [("S", 1), ("S", 3)], [1, 0]),            # 5-D, two sharded dims
@@ -1220,3 +1222,30 @@ def test_contiguous_shards_of_any_length(dtype):
         torch.cuda.synchronize()
         assert np.array_equal(md.cpu().numpy().reshape(mo.shape), mo), (dtype, args)
         assert_float_bits_equal(to_host(yd, dtype).reshape(yo.shape), yo, "dropout_add %s %s" % (dtype, args), dtype=dtype)
+
+
+def test_bench_line_keeps_its_contract():
+    """bench.py on this GPU, shortened: ONE JSON line with the keys the benchmark contract names, the roofline and
+    CPU-baseline objects included, and a throughput that is neither above the HBM peak nor implausibly low."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "5", "--warmup", "2", "--no-extra"],
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=240)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [l for l in res.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2 and d["vs_baseline"] is None and d["unit"] == "GB/s"
+    assert d["config"]["workload"].startswith("C5") and d["config"]["settle_seconds"] >= 0.25
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s" and abs(r["frac"] - r["achieved"] / 8000.0) < 1e-9
+    assert r["algorithmic_bytes_per_launch"] == 5 * d["config"]["elements"] and r["traffic"] is not None
+    assert 0.9 < r["traffic"] / r["algorithmic_bytes_per_launch"] < 1.1
+    assert 3000.0 < d["value"] < 8000.0 and 3000.0 < r["achieved"] < 8000.0
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["unit"] == "GB/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
