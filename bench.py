@@ -410,7 +410,7 @@ def design_choices(v, B, W, torch, once=False):
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -467,13 +467,23 @@ def design_choices(v, B, W, torch, once=False):
         for op, call in (("raw", lambda L: (lambda: L.vesrng_raw_u32(shr, 1, 0, oi))),
                          ("fp32 uniform", lambda L: (lambda: L.vesrng_uniform(shr, v.F32, 0.0, 1.0, 1, 0, of))),
                          ("fp32 normal", lambda L: (lambda: L.vesrng_normal(shr, v.F32, 0.0, 1.0, 1, 0, of)))):
-            entry("ragged %s fill, %d elements" % (op, nr), "large tile for raw and uniform from 2^23 elements, no staging for normal",
+            entry("ragged %s fill, %d elements" % (op, nr), "large tile for raw and uniform from 2^22 elements, no staging for normal",
                   [("library (kept)", call(v), 4 * nr),
                    ("no staging, element-aligned stores", call(variants["ragged"]), 4 * nr),
                    ("no staging, realigned across lanes (DPP)", call(variants["realign"]), 4 * nr),
                    ("staged, small tile", call(variants["smalltile"]), 4 * nr),
                    ("staged, large tile", call(variants["bigtile"]), 4 * nr),
-                   ("library's choice with the tile map per wavefront (scalar)", call(variants["wavetile"]), 4 * nr)])
+                   ("library's choice with the tile map per wavefront (scalar)", call(variants["wavetile"]), 4 * nr),
+                   ("library's choice with the general form of the tile map", call(variants["longmap"]), 4 * nr)])
+        # Fused bf16 dropout on the same shard (small tile): 5 bytes per element.
+        xr = torch.randn(nr, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+        orr = torch.empty_like(xr)
+        mr = torch.empty(nr, dtype=torch.uint8, device="cuda")
+        drop = lambda L: (lambda: L.vesrng_dropout(shr, v.BF16, 0.1, 1, 0, xr, orr, mr))
+        entry("ragged bf16 dropout, %d elements" % nr, "staged, short form of the tile map",
+              [("library (kept)", drop(v), 5 * nr), ("general form of the tile map", drop(variants["longmap"]), 5 * nr),
+               ("no staging", drop(variants["ragged"]), 5 * nr)])
+        del xr, orr, mr
     return res
 
 

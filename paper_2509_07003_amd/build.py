@@ -46,6 +46,9 @@ TARGETS = {
     # The staging kernel with its tile map worked out once per wavefront in scalar registers (runs of 64 blocks and more).
     "variant_wavetile": {"lib": "libvesrng_variant_wavetile.so", "sources": PRODUCT_SOURCES,
                          "defines": ["VESRNG_VARIANT_TAG=wavetile", "VESRNG_TILE_WAVE_MAP=1"]},
+    # The staging kernel with the general form of its tile map also where the short form applies.
+    "variant_longmap": {"lib": "libvesrng_variant_longmap.so", "sources": PRODUCT_SOURCES,
+                        "defines": ["VESRNG_VARIANT_TAG=longmap", "VESRNG_TILE_SAME_PHASE=0"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

@@ -62,6 +62,12 @@
 #ifndef VESRNG_TILE_WAVE_MAP
 #define VESRNG_TILE_WAVE_MAP 0
 #endif
+// 1 (always, in the library): column-like shards whose runs all start at the same position modulo 4 take the
+// short form of the staging kernel's tile map (plan.h: tile_spot_same_phase).  0 only in the measurement variant
+// that times the general form on them.
+#ifndef VESRNG_TILE_SAME_PHASE
+#define VESRNG_TILE_SAME_PHASE 1
+#endif
 // Measurement variants only: which operators may take the staging kernel.  -1 (the library): the
 // measured choice below; 0: none; 1: every operator, small tile only; 2: every operator, large tile
 // wherever the kernel has one.
@@ -480,7 +486,12 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 // UPT: aligned units a thread takes out of the tile in stage B (the tile is up to kThreads * UPT
 // units).  WAVE (measurement variant only): runs have at least 64 blocks and stage A works the tile map out
 // once per wavefront in scalar registers (plan.h: tile_wave) instead of once per lane.
-template <int OP, int DT, typename IT, int NOUT, int UPT, bool WAVE>
+// How stage A of the staging kernel finds where a generator block lands (plan.h).
+constexpr int kTileMapBlock = 0;      // per block, any box-shaped shard
+constexpr int kTileMapWave = 1;       // per wavefront (measurement variant only)
+constexpr int kTileMapSamePhase = 2;  // per block, short form: one axis of runs, one phase, 32-bit indices
+
+template <int OP, int DT, typename IT, int NOUT, int UPT, int MAP>
 __global__ void __launch_bounds__(kThreads)
 tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, const void* xin, void* out,
              uint8_t* mask) {
@@ -502,12 +513,14 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
   // Stage A: one block per thread (one pass for 4-byte units, two for bfloat16 units).
   for (IT k = threadIdx.x; k < count; k += kThreads) {
     TileSpot spot;
-    if constexpr (WAVE) {
+    if constexpr (MAP == kTileMapWave) {
       // Lane 0 of the wave holds the wave's first block number (lanes run out at the top end only).
       const uint64_t k64 = static_cast<uint64_t>(k);
       const uint64_t kw = (static_cast<uint64_t>(first_lane(static_cast<uint32_t>(k64 >> 32))) << 32) |
                           first_lane(static_cast<uint32_t>(k64));
       spot = tile_spot_of_lane(tile_wave<NOUT>(plan, i0, lim, static_cast<IT>(wa + static_cast<IT>(kw))), threadIdx.x & 63u);
+    } else if constexpr (MAP == kTileMapSamePhase) {
+      spot = tile_spot_same_phase(plan, ta, i0, lim, wa + k);
     } else {
       spot = tile_spot<NOUT>(plan, i0, lim, static_cast<IT>(wa + k));
     }
@@ -545,28 +558,27 @@ tiled_kernel(const PlanT<IT> plan, const OpParams prm, const TileArgs<IT> ta, co
     }
     return;
   }
-  for (uint32_t t = threadIdx.x; t < ta.tile_units; t += kThreads) {
-    const uint64_t u = static_cast<uint64_t>(blockIdx.x) * ta.tile_units + t;
-    const uint64_t e0 = u * V;
-    if (e0 >= i1) break;
-    if (e0 + V <= i1) {
-      uint32_t v[V];
+  // Indices relative to the tile fit 32 bits; the tile's first unit is the same for all threads.
+  const uint64_t u0 = static_cast<uint64_t>(blockIdx.x) * ta.tile_units;
+  const uint32_t whole = static_cast<uint32_t>(lim) / static_cast<uint32_t>(V);  // whole units of the tile
+  for (uint32_t t = threadIdx.x; t < whole; t += kThreads) {
+    uint32_t v[V];
 #pragma unroll
-      for (int q = 0; q < V / 4; ++q) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(&tile[t * V + 4 * q]);
+    for (int q = 0; q < V / 4; ++q) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(&tile[t * V + 4 * q]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[4 * q + e] = w[e];
-      }
-      u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
-      if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
-      if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + u);
-      emit_unit<OP, DT>(v, prm, xv, rv, u, out, mask);
-    } else {
-      // The last unit of a shard whose size is not a multiple of the unit.
-      for (uint64_t i = e0; i < i1; ++i)
-        emit_element<OP, DT>(tile[i - i0], prm, xin, static_cast<int64_t>(i), out, mask);
+      for (int e = 0; e < 4; ++e) v[4 * q + e] = w[e];
     }
+    const uint64_t u = u0 + t;
+    u32x4 xv = {0u, 0u, 0u, 0u}, rv = {0u, 0u, 0u, 0u};
+    if constexpr (kIsDropout<OP>) xv = __builtin_nontemporal_load(static_cast<const u32x4*>(xin) + u);
+    if constexpr (OP == kOpDropoutAdd) rv = __builtin_nontemporal_load(static_cast<const u32x4*>(prm.residual) + u);
+    emit_unit<OP, DT>(v, prm, xv, rv, u, out, mask);
   }
+  // The last unit of a shard whose size is not a multiple of the unit (only the shard's last tile has one).
+  if (threadIdx.x == (whole & (kThreads - 1)))
+    for (uint32_t i = whole * V; i < static_cast<uint32_t>(lim); ++i)
+      emit_element<OP, DT>(tile[i], prm, xin, static_cast<int64_t>(i0 + i), out, mask);
 }
 
 // ---- ragged / general kernels ----------------------------------------------------
@@ -829,25 +841,38 @@ constexpr bool kTileable =
 template <int OP, int DT>
 constexpr bool kTileable = (VESRNG_TILING != 0);
 #endif
-// Staged through LDS, the raw and fp32 uniform fills are bound by the latency of a workgroup's life,
-// not by arithmetic or LDS, so on LARGE shards they gain from four units per thread (measured on
-// column shards of 11 M to 358 M elements: raw 4.3-5.1 -> 5.0-5.75 TB/s, uniform 4.3-4.9 -> 4.7-5.5);
-// on small shards the four times fewer workgroups no longer fill the chip.  The fp32 normal fill
-// is bound by instruction issue instead and is fastest without staging at every size (5.0 TB/s
-// against 4.1 small tile / 4.8 large tile); dropout and randint, which issue more memory
-// instructions per unit, lose with the large tile and keep one unit.
+// Staged through LDS, the raw and fp32 uniform fills gain from four units per thread on all but small
+// shards (measured on column shards of 5.6 M to 358 M elements, short tile map: raw 3.7-5.3 -> 4.0-6.6 TB/s,
+// uniform 3.6-5.1 -> 3.9-6.3); on small shards the four times fewer workgroups no longer fill the chip.
+// The fp32 normal fill is bound by instruction issue: the large tile and no staging at all come out
+// within a few percent of each other at every size (4.4-5.3 TB/s either way, which one leads changes
+// with the run length), the small tile 10-20 % behind; it keeps the kernel without staging.  Dropout
+// and randint, which issue more memory instructions per unit, lose with the large tile and keep one unit.
 template <int OP, int DT>
 constexpr bool kBigTileable = (VESRNG_TILING == -1 || VESRNG_TILING == 2) &&
                               ((OP == kOpRaw || OP == kOpUniform || (OP == kOpNormal && VESRNG_TILING == 2)) &&
                                UnitOf<OP, DT>::kElems == 4);
-// Smallest shard that takes the big tile (measured crossover: between 5.6 M and 11 M elements).
+// Smallest shard that takes the big tile (measured: level at 2.8 M elements, 6 % ahead at 5.6 M).
 #ifdef VESRNG_BIG_TILE_MIN_ELEMS  // measurement variants only: force one tile size
 template <int OP>
 constexpr uint64_t kBigTileMinElems = VESRNG_BIG_TILE_MIN_ELEMS;
 #else
 template <int OP>
-constexpr uint64_t kBigTileMinElems = 1ull << 23;
+constexpr uint64_t kBigTileMinElems = 1ull << 22;
 #endif
+
+template <int OP, int DT, typename IT, int NOUT, int UPT>
+hipError_t launch_tiled(const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel, dim3 grid, dim3 block,
+                        const OpParams& prm, const void* x, void* out, uint8_t* mask, hipStream_t stream) {
+  const TileArgs<IT> ta = make_tile_args(plan, tile_units, local_numel);
+  if constexpr (VESRNG_TILE_WAVE_MAP != 0)
+    if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
+      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapWave>, grid, block, stream, plan, prm, ta, x, out, mask);
+  if constexpr (VESRNG_TILE_SAME_PHASE != 0 && NOUT == 1 && std::is_same<IT, uint32_t>::value)
+    if (ta.same_phase)
+      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapSamePhase>, grid, block, stream, plan, prm, ta, x, out, mask);
+  return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapBlock>, grid, block, stream, plan, prm, ta, x, out, mask);
+}
 
 template <int OP, int DT, typename IT, int NOUT>
 hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel,
@@ -868,24 +893,11 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
           return enqueue(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, stream, plan, prm, x, out, mask);
       return enqueue(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, stream, plan, prm, x, out, mask);
     case kTiled:
-      if constexpr (kTileable<OP, DT>) {
-        const TileArgs<IT> ta{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel};
-        if constexpr (VESRNG_TILE_WAVE_MAP != 0)
-          if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
-            return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1, true>, grid, block, stream, plan, prm, ta, x, out, mask);
-        return enqueue(tiled_kernel<OP, DT, IT, NOUT, 1, false>, grid, block, stream, plan, prm, ta, x, out, mask);
-      }
+      if constexpr (kTileable<OP, DT>) return launch_tiled<OP, DT, IT, NOUT, 1>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
       break;
     case kTiledBig:
-      if constexpr (kBigTileable<OP, DT>) {
-        const TileArgs<IT> ta{DivOf<IT>::make(plan.run_len), static_cast<IT>(tile_units), local_numel};
-        if constexpr (VESRNG_TILE_WAVE_MAP != 0)
-          if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
-            return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits, true>, grid, block, stream, plan, prm, ta, x, out,
-                           mask);
-        return enqueue(tiled_kernel<OP, DT, IT, NOUT, kBigTileUnits, false>, grid, block, stream, plan, prm, ta, x, out,
-                       mask);
-      }
+      if constexpr (kBigTileable<OP, DT>)
+        return launch_tiled<OP, DT, IT, NOUT, kBigTileUnits>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
       break;
     case kRagged:
       return enqueue(ragged_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);

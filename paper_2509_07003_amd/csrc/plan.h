@@ -142,7 +142,32 @@ struct TileArgs {
   typename PlanT<IT>::Div run_len_div;  // divides by the run length
   IT tile_units;                        // aligned units of the local tensor per tile
   uint64_t local_numel;
+  // The short form of the tile map (tile_spot_same_phase below) and its two constants.
+  uint32_t same_phase;  // 1: the short form applies
+  uint32_t dblock;      // stride / 4 - units_per_run
+  uint32_t drel;        // run_len - 4 * units_per_run modulo 2^32 (zero or a small negative number)
 };
+
+// Fills the tile arguments for a plan whose units_per_run counts generator blocks per run.  The short form
+// of the map needs: 32-bit indices, ONE axis of runs, a stride between runs that is a multiple of four
+// (so every run starts at the same position modulo 4 and units_per_run is exact for every run) and at
+// least units_per_run blocks long, with a difference that fits 32 bits.
+template <typename IT>
+inline TileArgs<IT> make_tile_args(const PlanT<IT>& plan, uint64_t tile_units, uint64_t local_numel) {
+  TileArgs<IT> ta{};
+  ta.run_len_div = DivOf<IT>::make(plan.run_len);
+  ta.tile_units = static_cast<IT>(tile_units);
+  ta.local_numel = local_numel;
+  if (sizeof(IT) == 4 && plan.n_outer == 1 && plan.outer_stride[0] % 4 == 0) {
+    const uint64_t s4 = plan.outer_stride[0] >> 2, upr = static_cast<uint64_t>(plan.units_per_run);
+    if (s4 >= upr && s4 - upr <= 0xFFFFFFFFull) {
+      ta.same_phase = 1;
+      ta.dblock = static_cast<uint32_t>(s4 - upr);
+      ta.drel = static_cast<uint32_t>(plan.run_len) - 4u * static_cast<uint32_t>(upr);
+    }
+  }
+  return ta;
+}
 // A run of at least 64 blocks lets stage A work out the tile map once per wavefront (tile_wave).
 constexpr uint64_t kTileWaveMinBlocks = 64;
 
@@ -179,6 +204,27 @@ VESRNG_HD TileSpot tile_spot(const PlanT<IT>& plan, uint64_t i0, int32_t lim, IT
   s.rel = static_cast<int32_t>(run_lo + static_cast<ST>(4 * bi) - static_cast<ST>(static_cast<uint32_t>(run_pos) & 3u));
   s.lo = static_cast<int32_t>(run_lo > zero ? (run_lo < top ? run_lo : top) : zero);
   s.hi = static_cast<int32_t>(run_hi < top ? (run_hi > zero ? run_hi : zero) : top);
+  return s;
+}
+
+// The short form of the same map, for the shards make_tile_args marks (a column shard of a matrix whose
+// row length is a multiple of four is the common one).  With one phase for all runs, run r starts at
+// stream position pos0 + r * stride = 4 * (pos0 / 4 + r * stride / 4) + phase, so block w = r * upr + bi is
+//   block = pos0 / 4 + r * (stride / 4 - upr) + w,      rel = 4 w + r * (run_len - 4 upr) - (i0 + phase),
+// one division and two multiply-adds per block in 32-bit registers (rel modulo 2^32: its value lies within a
+// block of the tile).  upr is exact for every run, so each block number of a tile belongs to a run that
+// intersects the tile: run_lo < lim and run_hi > 0, and one-sided clamps give the same lo and hi.
+VESRNG_HD TileSpot tile_spot_same_phase(const PlanT<uint32_t>& plan, const TileArgs<uint32_t>& ta, uint64_t i0,
+                                        int32_t lim, uint32_t w) {
+  const uint32_t run = plan.units_div.div(w);
+  const uint32_t i032 = static_cast<uint32_t>(i0);
+  const int32_t run_lo = static_cast<int32_t>(run * plan.run_len - i032);
+  const int32_t run_hi = run_lo + static_cast<int32_t>(plan.run_len);
+  TileSpot s;
+  s.block = (plan.pos0 >> 2) + static_cast<uint64_t>(run) * ta.dblock + w;
+  s.rel = static_cast<int32_t>(4u * w + run * ta.drel - (i032 + (static_cast<uint32_t>(plan.pos0) & 3u)));
+  s.lo = run_lo > 0 ? run_lo : 0;
+  s.hi = run_hi < lim ? run_hi : lim;
   return s;
 }
 

@@ -14,7 +14,8 @@
 //          " J j(0) .. j(numel-1)" from vesrng_global_index and " K ..." from
 //          vesrng_global_index_general; then " A status new_offset" of vesrng_advance_offset(0).
 //   T sharding offset unit_elems tileable big_tileable big_min_elems whole_blocks_only ntiles tile[ntiles]
-//       -> "T status flavour wide units_per_run tile_units n_tiles_total" and per requested tile
+//       -> "T status flavour wide units_per_run tile_units n_tiles_total short=0|1" (short: the short form of the
+//          tile map applies and was walked next to the general one) and per requested tile
 //          " | i0 lim count dummy_writes pos(0) .. pos(lim-1)": the stream position whose value
 //          lands in each slot; -1 = never written, -2 = written twice.
 #include <cstdint>
@@ -126,6 +127,15 @@ void emulate_tile(const PlanT<IT>& plan, const TileArgs<IT>& ta, uint64_t unit_e
         std::printf(" | OUT-OF-TILE wave-map-mismatch-at-block-%llu", static_cast<unsigned long long>(k));
       spot = ws;
     }
+    // The short form of the map, where the library would take it: the same four fields for every block.
+    if constexpr (NOUT == 1 && sizeof(IT) == 4) {
+      if (ta.same_phase) {
+        const TileSpot sp = tile_spot_same_phase(plan, ta, i0, lim, static_cast<IT>(wa + k));
+        if (sp.block != spot.block || sp.rel != spot.rel || sp.lo != spot.lo || sp.hi != spot.hi)
+          std::printf(" | OUT-OF-TILE short-map-mismatch-at-block-%llu", static_cast<unsigned long long>(k));
+        spot = sp;
+      }
+    }
     // The kernel's own choice between the interior path and the edge path.
     const int32_t rel = spot.rel, lo = spot.lo, hi = spot.hi;
     for (int e = 0; e < 4; ++e) {
@@ -157,7 +167,8 @@ template <typename IT>
 void tiles_typed(const Geometry& g, const RunShape& rs, uint64_t offset, const LaunchChoice& c, uint64_t unit_elems,
                  const std::vector<uint64_t>& tiles) {
   const PlanT<IT> plan = make_plan<IT>(g, rs, offset, c.units_per_run);
-  const TileArgs<IT> ta{DivOf<IT>::make(plan.run_len), static_cast<IT>(c.tile_units), static_cast<uint64_t>(g.local_numel)};
+  const TileArgs<IT> ta = make_tile_args(plan, c.tile_units, static_cast<uint64_t>(g.local_numel));
+  std::printf(" short=%u", ta.same_phase);
   for (uint64_t t : tiles) {
     switch (plan.n_outer) {
       case 0: emulate_tile<IT, 0>(plan, ta, unit_elems, t); break;

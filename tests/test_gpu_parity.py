@@ -1165,7 +1165,7 @@ def test_generator_sequence_of_operators_matches_one_device_doing_the_same_seque
 
 
 def test_large_ragged_fp32_fills():
-    """Ragged column shards big enough (2^23 elements and more) to take the large-tile form of the staging
+    """Ragged column shards big enough (2^22 elements and more) to take the large-tile form of the staging
     kernel - raw and uniform fp32 - and the fp32 normal fill, which stays on the kernel without staging at
     every size, against the threaded oracle, with the rows' phases equal (row length 4100) and unequal (4101)."""
     seed, offset = 31337, 1 << 33
@@ -1187,6 +1187,39 @@ def test_large_ragged_fp32_fills():
         got = gpu_fill("normal", "f32", args, seed, offset, mean=-1.0, std=3.0)
         check_normal(got, args, "f32", -1.0, 3.0, seed, offset, "normal f32 %s" % (args,))
         del got
+
+
+def test_column_shards_whose_runs_share_one_phase():
+    """Ragged shards with ONE axis of runs and a stride between runs that is a multiple of four (a column shard of
+    a matrix whose row length is a multiple of four; rows of a padded tensor): the staging kernel takes the short
+    form of its tile map.  Small tile and large tile, every operator that is staged, every phase, and strides
+    that a run's generator blocks fill exactly (and overfill by one: the general form then serves)."""
+    seed, offset = 8642, 1 << 34
+    cases = [([1000, 1000], [3], [("S", 1)], [1]),                    # runs of 334 at phase 2
+             ([513, 2048], [5], [("S", 1)], [3]),                     # runs of 410 at phase 2
+             ([777, 404], [4], [("S", 1)], [3]),                      # runs of 101 at phase 3
+             ([3000, 2, 17], [2], [("S", 1)], [1], [20, 3, 1]),       # stride 20 = 4 x (blocks per run): exact fit
+             ([3000, 2, 18], [2], [("S", 1)], [1], [20, 3, 1]),       # one block more than the stride holds
+             ([3000, 2, 19], [2], [("S", 1)], [1], [20, 1, 1]),       # phase 1
+             ([5000, 1030], [1], [("R",)], [0], [1032, 1]),           # phase 0, ragged only at the run's end (large tile)
+             ([5000, 1032], [2], [("S", 1)], [1])]                    # runs of 516 from column 516 (aligned: not staged)
+    for args in cases:
+        n = oracle.local_shape(*args[:4])[1]
+        say("one-phase runs %s" % (args,))
+        got = gpu_fill("raw", None, args, seed, offset)
+        assert np.array_equal(got, oracle.raw_u32(args, seed, offset, threads=THREADS)), args
+        got = gpu_fill("uniform", "f32", args, seed, offset, low=-1.0, high=2.0)
+        want = oracle.uniform(args, oracle.F32, -1.0, 2.0, seed, offset, threads=THREADS)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), args
+        got = gpu_fill("randint", None, args, seed, offset, low=-5, high=(1 << 32) - 5)
+        assert np.array_equal(got, oracle.randint(args, -5, (1 << 32) - 5, seed, offset, threads=THREADS)), args
+        xf = W.adversarial_f32(n, seed=11)
+        for dtype, code in (("f32", oracle.F32), ("bf16", oracle.BF16), ("f16", oracle.F16)):
+            x = xf if dtype == "f32" else (W.bf16_bits_from_f32(xf) if dtype == "bf16" else W.f16_bits_from_f32(xf))
+            yo, mo = oracle.dropout(args, code, 0.3, seed, offset, x)
+            y, m = gpu_dropout(dtype, args, 0.3, seed, offset, x)
+            assert np.array_equal(m, mo), (args, dtype)
+            assert_float_bits_equal(y, yo, "dropout %s %s" % (dtype, args), dtype=dtype)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])

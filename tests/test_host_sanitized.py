@@ -177,7 +177,7 @@ def parse_t(line):
     t = head.split()
     assert t[0] == "T" and t[1] == "0", line[:200]
     res = {"flavour": int(t[2]), "wide": int(t[3]), "units_per_run": int(t[4]), "tile_units": int(t[5]),
-           "n_tiles": int(t[6]), "tiles": []}
+           "n_tiles": int(t[6]), "short": (t[7] == "short=1") if len(t) > 7 else False, "tiles": []}
     for tile in tiles:
         w = tile.split()
         assert w[0] != "OUT-OF-TILE", "the kernel would write outside its LDS tile: " + tile[:100]
@@ -249,3 +249,32 @@ def test_tile_map_of_column_shards_with_equal_and_unequal_phases(host_check):
         head, _ = check_tiles(host_check, words, offset, unit_elems, big, position_of, n,
                               [n // 2, n // 3, 2 ** 31] if n > 2 ** 31 else [n // 2, n // 3])
         assert head["wide"] == (1 if n >= 2 ** 30 else 0)
+        # The short form of the map serves the narrow shards whose row length is a multiple of four; check_tiles
+        # has then walked it next to the general form (the program reports any field that differs).
+        assert head["short"] == (cols % 4 == 0 and n < 2 ** 30)
+
+
+def test_short_tile_map_at_its_limits(host_check):
+    """The short form of the tile map (one division and two multiply-adds per block) needs a stride between runs
+    of at least as many generator blocks as a run can touch.  Rows of a padded tensor, reached through the
+    global stride, give runs that nearly fill their stride: stride / 4 equal to the blocks per run (taken),
+    one below (refused: the general form serves), and every phase; each slot is still written exactly once
+    with its own position."""
+    rows, offset = 3000, 1 << 20
+    for length, lead, row_stride, want_short in ((17, 3, 20, True), (18, 3, 20, False), (17, 0, 20, True),
+                                                 (19, 1, 20, True), (18, 2, 20, True), (33, 7, 40, True),
+                                                 (38, 1, 40, True), (38, 3, 40, False), (21, 2, 24, True)):
+        # Shape [rows, 2, length] with strides [row_stride, lead, 1]; the rank holds index 1 of the middle dimension,
+        # so its runs start at lead + r * row_stride (phase lead % 4).
+        words = sharding_words([rows, 2, length], [2], [("S", 1)], [1], stride=[row_stride, lead, 1])
+        if lead == 0:   # phase 0 from a plain replicated tensor with padded rows
+            words = sharding_words([rows, length], [1], [("R",)], [0], stride=[row_stride, 1])
+
+        def position_of(i, length=length, lead=lead, row_stride=row_stride):
+            return np.uint64(offset + lead) + (i // np.uint64(length)) * np.uint64(row_stride) + i % np.uint64(length)
+
+        n = rows * length
+        for unit_elems in (4, 8):
+            head, _ = check_tiles(host_check, words, offset, unit_elems, 0, position_of, n, [n // 2, n // 3, n - 5])
+            assert head["short"] == want_short, (length, lead, row_stride)
+            assert head["units_per_run"] == (lead % 4 + length + 3) // 4
