@@ -207,7 +207,10 @@ def measured_ceilings(B, torch):
     out = {"store_only_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_STORE, units, None, a), nbytes),
            "store_unaligned_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_STORE_UNALIGNED, units, None, a), nbytes),
            "copy_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_COPY, units, a, b), 2 * nbytes),
-           "dropout_traffic_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
+           # The dropout kernel's loads and stores without its arithmetic, launched as the library launches large
+           # masked dropout (at most seven resident waves per SIMD), and at the hardware's eight.
+           "dropout_traffic_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC_7_WAVES, units, a, b, m), 2.5 * nbytes),
+           "dropout_traffic_8_waves_gb_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_DROPOUT_TRAFFIC, units, a, b, m), 2.5 * nbytes),
            "philox_only_gblocks_per_s": rate(lambda: B.vesrng_bench_probe(B.PROBE_PHILOX, blocks, None, a), blocks)}
     # Issue rates: cycles a SIMD needs per wave-instruction of each class, 16 workgroups per compute unit.
     cus, sclk_khz = B.vesrng_bench_device_info()[:2]
@@ -403,14 +406,16 @@ def design_choices(v, B, W, torch, once=False):
            ("ordinary loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN, units, a, b, m), 2.5 * nbytes),
            ("sc1 nt loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_SC1, units, a, b, m), 2.5 * nbytes),
            ("sc0 sc1 loads", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1, units, a, b, m), 2.5 * nbytes),
-           ("two units per thread, 16-byte mask stores", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_WIDE_MASK, units, a, b, m), 2.5 * nbytes)])
+           ("two units per thread, 16-byte mask stores", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_WIDE_MASK, units, a, b, m), 2.5 * nbytes),
+           ("kept pattern, at most seven resident waves per SIMD", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_7_WAVES, units, a, b, m), 2.5 * nbytes),
+           ("kept pattern, at most six", lambda: probe(B.PROBE_DROPOUT_TRAFFIC_6_WAVES, units, a, b, m), 2.5 * nbytes)])
     blocks = 1 << 30
     entry("three-way XOR of the generator (generator only)", "v_bitop3_b32",
           [("v_bitop3_b32 (kept)", lambda: probe(B.PROBE_PHILOX, blocks, None, a), blocks * 16),
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -419,9 +424,10 @@ def design_choices(v, B, W, torch, once=False):
     y = torch.empty_like(x)
     mask = torch.empty(n5, dtype=torch.uint8, device="cuda")
     drop = lambda L: (lambda: L.vesrng_dropout(sh5, v.BF16, 0.1, 1234, 0, x, y, mask))
-    entry("C5 fused dropout: argument-fetch pinning, store bits", "pinned, sc1 nt",
+    entry("C5 fused dropout: argument-fetch pinning, store bits, resident waves", "pinned, sc1 nt, at most seven waves per SIMD",
           [("library (kept)", drop(v), 5 * n5), ("without the pinning", drop(variants["nopin"]), 5 * n5),
-           ("plain non-temporal stores", drop(variants["ntstore"]), 5 * n5)])
+           ("plain non-temporal stores", drop(variants["ntstore"]), 5 * n5),
+           ("eight resident waves per SIMD (no cap)", drop(variants["nocap"]), 5 * n5)])
     del x, y, mask
     n = 1 << 28
     shu = v.Sharding([n], [1], [("R",)], [0])

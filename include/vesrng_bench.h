@@ -46,7 +46,12 @@ typedef enum {
                                                    bytes of the pair leave as ONE 16-byte store per thread */
   VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN = 12, /* ordinary loads instead of non-temporal ones */
   VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC1 = 13,   /* loads with the cache-control bits sc1 nt */
-  VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1 = 14 /* loads with sc0 sc1 (system scope) */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1 = 14, /* loads with sc0 sc1 (system scope) */
+  /* Resident waves: the kept traffic pattern (kind 2) launched with 21 KiB / 26 KiB of untouched dynamic LDS per
+     workgroup, so that a compute unit holds seven / six workgroups of four waves instead of eight.  The library's
+     large dropout launches that write a mask run in the seven-wave form. */
+  VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES = 15,
+  VESRNG_PROBE_DROPOUT_TRAFFIC_6_WAVES = 16
 } vesrng_probe_kind;
 
 VESRNG_API vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t units, const void* in, void* out,

@@ -12,7 +12,8 @@ from .binding import (BF16, F16, F32, Sharding, _check, _dev, _stream, load_libr
 (PROBE_STORE, PROBE_COPY, PROBE_DROPOUT_TRAFFIC, PROBE_PHILOX, PROBE_STORE_NT, PROBE_STORE_PLAIN,
  PROBE_STORE_GRID_STRIDE, PROBE_STORE_UNALIGNED, PROBE_DROPOUT_TRAFFIC_NT, PROBE_PHILOX_TWO_XOR,
  PROBE_STORE_4_PER_THREAD, PROBE_DROPOUT_TRAFFIC_WIDE_MASK, PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN,
- PROBE_DROPOUT_TRAFFIC_LOAD_SC1, PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1) = range(15)
+ PROBE_DROPOUT_TRAFFIC_LOAD_SC1, PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1, PROBE_DROPOUT_TRAFFIC_7_WAVES,
+ PROBE_DROPOUT_TRAFFIC_6_WAVES) = range(17)
 
 # vesrng_alu_class, in the header's order
 ALU_CLASSES = ["mad_u64_u32", "bitop3_b32", "add_u32", "fma_f32", "mul_f32", "cvt_f32_u32", "log_f32", "sqrt_f32",
@@ -91,3 +92,7 @@ class Variant:
     def vesrng_dropout(self, sharding, dtype, p, seed, offset, x, y, mask=None, stream=None):
         _check(self._lib.vesrng_dropout(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(y), _dev(mask),
                                         _stream(stream, x, y, mask)))
+
+    def vesrng_dropout_add(self, sharding, dtype, p, seed, offset, x, residual, y, mask=None, stream=None):
+        _check(self._lib.vesrng_dropout_add(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(residual),
+                                            _dev(y), _dev(mask), _stream(stream, x, residual, y, mask)))

@@ -49,6 +49,9 @@ TARGETS = {
     # The staging kernel with the general form of its tile map also where the short form applies.
     "variant_longmap": {"lib": "libvesrng_variant_longmap.so", "sources": PRODUCT_SOURCES,
                         "defines": ["VESRNG_VARIANT_TAG=longmap", "VESRNG_TILE_SAME_PHASE=0"]},
+    # Fused dropout that writes a mask at the hardware's full eight resident waves per SIMD (no cap at seven).
+    "variant_nocap": {"lib": "libvesrng_variant_nocap.so", "sources": PRODUCT_SOURCES,
+                      "defines": ["VESRNG_VARIANT_TAG=nocap", "VESRNG_CAP_MASKED_DROPOUT_WAVES=0"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

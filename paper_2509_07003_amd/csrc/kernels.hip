@@ -65,6 +65,12 @@
 // 1 (always, in the library): column-like shards whose runs all start at the same position modulo 4 take the
 // short form of the staging kernel's tile map (plan.h: tile_spot_same_phase).  0 only in the measurement variant
 // that times the general form on them.
+// 1 (always, in the library): large aligned launches of fused dropout that also write the mask run with at most
+// seven resident waves per SIMD instead of the hardware's eight (see kWaveCapLdsBytes).  0 only in the measurement
+// variant that times them uncapped.
+#ifndef VESRNG_CAP_MASKED_DROPOUT_WAVES
+#define VESRNG_CAP_MASKED_DROPOUT_WAVES 1
+#endif
 #ifndef VESRNG_TILE_SAME_PHASE
 #define VESRNG_TILE_SAME_PHASE 1
 #endif
@@ -803,14 +809,30 @@ theta_kernel(const ThetaPlan tp, const OpParams prm, const void* xin, void* out,
 
 // Enqueues `kernel` and returns the launch's own status (hipGetLastError would also report,
 // and clear, an error some other code left behind).
+// `unused_lds_bytes` of dynamic LDS that the kernel never touches limit how many workgroups a compute unit holds
+// at once (160 KiB of LDS per compute unit).
 template <typename... Params, typename... Args>
-hipError_t enqueue(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+hipError_t enqueue_with_lds(void (*kernel)(Params...), dim3 grid, dim3 block, size_t unused_lds_bytes, hipStream_t stream,
+                            Args... args) {
   static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
   std::tuple<std::remove_cv_t<Params>...> values{args...};
   void* ptrs[sizeof...(Params)];
   fill_pointers(values, ptrs, std::index_sequence_for<Params...>{});
-  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, unused_lds_bytes, stream);
 }
+template <typename... Params, typename... Args>
+hipError_t enqueue(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+  return enqueue_with_lds(kernel, grid, block, 0, stream, args...);
+}
+
+// Seven resident waves per SIMD instead of eight for fused dropout WITH a mask, on launches that stream far more than
+// the last-level cache holds: a workgroup is four waves, one per SIMD, so a compute unit holds eight workgroups; 21 KiB
+// of untouched dynamic LDS each let seven fit in its 160 KiB.  Measured in one run on 2^29-element shards: bf16 dropout
+// with mask 6.52 -> 6.67 TB/s, fp32 with mask 6.53 -> 6.64; six waves gain less (6.65), five lose a tenth.  The same
+// cap costs the kernels with ONE store stream (fills, dropout without mask: -0.3 to -1.7 %) and the launches that fit
+// the cache (-0.7 % on 17 M elements), so only these take it.
+constexpr size_t kWaveCapLdsBytes = 21 * 1024;
+constexpr uint64_t kWaveCapMinUnits = 1ull << 23;
 
 template <int OP, int DT>
 hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm, const void* x, void* out,
@@ -887,11 +909,15 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
   switch (flavour) {
-    case kAligned:
+    case kAligned: {
+      size_t cap = 0;
+      if constexpr (kIsDropout<OP> && VESRNG_CAP_MASKED_DROPOUT_WAVES != 0)
+        if (mask != nullptr && plan.total_units >= kWaveCapMinUnits) cap = kWaveCapLdsBytes;
       if constexpr (NOUT != 0 && VESRNG_WAVE_UNIFORM_RUNS != 0)
         if (plan.wave_runs)
-          return enqueue(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, stream, plan, prm, x, out, mask);
-      return enqueue(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, stream, plan, prm, x, out, mask);
+          return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, cap, stream, plan, prm, x, out, mask);
+      return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, cap, stream, plan, prm, x, out, mask);
+    }
     case kTiled:
       if constexpr (kTileable<OP, DT>) return launch_tiled<OP, DT, IT, NOUT, 1>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
       break;

@@ -295,6 +295,13 @@ extern "C" vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t uni
         hipLaunchKernelGGL(dropout_traffic_probe<kNonTemporal>, grid, block, 0, stream, i, o, static_cast<u32x2*>(out2),
                            units);
       break;
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES:
+    case VESRNG_PROBE_DROPOUT_TRAFFIC_6_WAVES:
+      if (!in || !out2) return VESRNG_ERR_NULL;
+      hipLaunchKernelGGL(dropout_traffic_probe<kStream>, grid, block,
+                         (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES ? 21u : 26u) * 1024u, stream, i, o,
+                         static_cast<u32x2*>(out2), units);
+      break;
     case VESRNG_PROBE_DROPOUT_TRAFFIC_WIDE_MASK:
       if (!in || !out2) return VESRNG_ERR_NULL;
       hipLaunchKernelGGL(dropout_traffic_wide_mask_probe, dim3(static_cast<uint32_t>((blocks + 1) / 2)), block, 0, stream, i,

@@ -747,7 +747,8 @@ def test_ceiling_probes_do_what_they_say():
     bb = torch.zeros_like(a)
     b.vesrng_bench_probe(b.PROBE_COPY, units, a, bb)
     for kind in (b.PROBE_DROPOUT_TRAFFIC, b.PROBE_DROPOUT_TRAFFIC_NT, b.PROBE_DROPOUT_TRAFFIC_LOAD_PLAIN,
-                 b.PROBE_DROPOUT_TRAFFIC_LOAD_SC1, b.PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1):
+                 b.PROBE_DROPOUT_TRAFFIC_LOAD_SC1, b.PROBE_DROPOUT_TRAFFIC_LOAD_SC0SC1,
+                 b.PROBE_DROPOUT_TRAFFIC_7_WAVES, b.PROBE_DROPOUT_TRAFFIC_6_WAVES):
         m = torch.zeros(units * 2, dtype=torch.int32, device=DEV)
         c = torch.zeros_like(a)
         b.vesrng_bench_probe(kind, units, a, c, m)
@@ -823,6 +824,53 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
         assert np.array_equal(y.view(torch.int16).cpu().numpy().view(np.uint16).reshape(lshape), yo), replay
         err = np.abs(z.cpu().numpy().astype(np.float64) - zo)
         assert (err <= 1e-6 * np.maximum(np.abs(zo), 1.0)).all(), replay
+
+
+def test_large_masked_dropout_launch_form_in_a_graph_and_against_the_oracle():
+    """Aligned fused dropout that writes a mask is launched with at most seven resident waves per SIMD once it has
+    2^23 units and more (untouched dynamic LDS per workgroup).  The values must not depend on that: a 2^26-element
+    bf16 shard and a 2^25-element fp32 shard against the oracle on sampled windows, against the same call without a
+    mask (launched at the hardware's eight waves), and captured in a HIP graph and replayed."""
+    seed, offset = 97531, 1 << 35
+    rng = np.random.default_rng(5)
+    for dtype, code, n in (("bf16", oracle.BF16, 1 << 26), ("f32", oracle.F32, 1 << 25)):
+        args = ([n], [1], [("R",)], [0])
+        sh = v.Sharding(*args)
+        x = torch.randn(n, dtype=torch.float32, device=DEV)
+        x = x.to(torch.bfloat16) if dtype == "bf16" else x
+        y = torch.empty_like(x)
+        y2 = torch.empty_like(x)
+        mask = torch.empty(n, dtype=torch.uint8, device=DEV)
+        say("large masked dropout %s" % dtype)
+        v.vesrng_dropout(sh, DT[dtype][1], 0.2, seed, offset, x, y, mask)
+        v.vesrng_dropout(sh, DT[dtype][1], 0.2, seed, offset, x, y2, None)       # the launch form without the cap
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16 if dtype == "bf16" else torch.int32),
+                           y2.view(torch.int16 if dtype == "bf16" else torch.int32))
+        x_host = to_host(x, dtype)
+        for begin in [0, n - 4096] + [int(b) for b in rng.integers(0, n - 4096, size=6)]:
+            yo, mo = oracle.dropout(args, code, 0.2, seed, offset, x_host, i_begin=begin, i_end=begin + 4096)
+            assert np.array_equal(mask[begin:begin + 4096].cpu().numpy(), mo.reshape(-1)[begin:begin + 4096]), (dtype, begin)
+            assert_float_bits_equal(to_host(y[begin:begin + 4096], dtype), yo.reshape(-1)[begin:begin + 4096],
+                                    "large masked dropout %s at %d" % (dtype, begin), dtype=dtype)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        y3 = torch.empty_like(x)
+        m3 = torch.empty_like(mask)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                v.vesrng_dropout(sh, DT[dtype][1], 0.2, seed, offset, x, y3, m3)
+        for replay in range(2):
+            y3.fill_(3.0)
+            m3.fill_(9)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(m3, mask), (dtype, replay)
+            assert torch.equal(y3.view(torch.int16 if dtype == "bf16" else torch.int32),
+                               y.view(torch.int16 if dtype == "bf16" else torch.int32)), (dtype, replay)
+        del x, y, y2, y3, mask, m3
 
 
 @pytest.mark.parametrize("label,shape", [("262 KB", [8, 16, 8, 8, 8]), ("64 MB", [16, 32, 32, 32, 32]),
