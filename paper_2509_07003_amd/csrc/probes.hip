@@ -80,8 +80,10 @@ __global__ void __launch_bounds__(kThreads) copy_probe(const u32x4* in, u32x4* o
   vesrng::stream_store(__builtin_nontemporal_load(in + t), out + t);
 }
 
-// The bf16 dropout kernel's accesses with no arithmetic: 16 bytes in, 16 + 8 bytes out per thread.
-template <int FORM>
+// The bf16 dropout kernel's accesses with no arithmetic: 16 bytes in, 16 + 8 bytes out per thread.  WAVES only
+// names the launch form in a profiler's trace: 8 = plain, 7 / 6 = launched with 21 / 26 KiB of untouched dynamic
+// LDS per workgroup, so that a compute unit holds that many workgroups (of one wave per SIMD each).
+template <int FORM, int WAVES = 8>
 __global__ void __launch_bounds__(kThreads)
 dropout_traffic_probe(const u32x4* in, u32x4* out, u32x2* mask, uint64_t units) {
   const uint64_t t = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -298,9 +300,12 @@ extern "C" vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t uni
     case VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES:
     case VESRNG_PROBE_DROPOUT_TRAFFIC_6_WAVES:
       if (!in || !out2) return VESRNG_ERR_NULL;
-      hipLaunchKernelGGL(dropout_traffic_probe<kStream>, grid, block,
-                         (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES ? 21u : 26u) * 1024u, stream, i, o,
-                         static_cast<u32x2*>(out2), units);
+      if (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES)
+        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 7>), grid, block, 21u * 1024u, stream, i, o, static_cast<u32x2*>(out2),
+                           units);
+      else
+        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 6>), grid, block, 26u * 1024u, stream, i, o, static_cast<u32x2*>(out2),
+                           units);
       break;
     case VESRNG_PROBE_DROPOUT_TRAFFIC_WIDE_MASK:
       if (!in || !out2) return VESRNG_ERR_NULL;
