@@ -889,10 +889,12 @@ hipError_t launch_tiled(const PlanT<IT>& plan, uint64_t tile_units, uint64_t loc
   const TileArgs<IT> ta = make_tile_args(plan, tile_units, local_numel);
   if constexpr (VESRNG_TILE_WAVE_MAP != 0)
     if (static_cast<uint64_t>(plan.units_per_run) >= kTileWaveMinBlocks)
-      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapWave>, grid, block, stream, plan, prm, ta, x, out, mask);
+      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapWave>, grid, block, stream, plan, prm, ta, x, out,
+                     mask);
   if constexpr (VESRNG_TILE_SAME_PHASE != 0 && NOUT == 1 && std::is_same<IT, uint32_t>::value)
     if (ta.same_phase)
-      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapSamePhase>, grid, block, stream, plan, prm, ta, x, out, mask);
+      return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapSamePhase>, grid, block, stream, plan, prm, ta, x, out,
+                     mask);
   return enqueue(tiled_kernel<OP, DT, IT, NOUT, UPT, kTileMapBlock>, grid, block, stream, plan, prm, ta, x, out, mask);
 }
 
@@ -915,15 +917,19 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
         if (mask != nullptr && plan.total_units >= kWaveCapMinUnits) cap = kWaveCapLdsBytes;
       if constexpr (NOUT != 0 && VESRNG_WAVE_UNIFORM_RUNS != 0)
         if (plan.wave_runs)
-          return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, cap, stream, plan, prm, x, out, mask);
-      return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, cap, stream, plan, prm, x, out, mask);
+          return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, cap, stream, plan, prm, x, out,
+                                  mask);
+      return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, false>, grid, block, cap, stream, plan, prm, x, out,
+                              mask);
     }
     case kTiled:
-      if constexpr (kTileable<OP, DT>) return launch_tiled<OP, DT, IT, NOUT, 1>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
+      if constexpr (kTileable<OP, DT>)
+        return launch_tiled<OP, DT, IT, NOUT, 1>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
       break;
     case kTiledBig:
       if constexpr (kBigTileable<OP, DT>)
-        return launch_tiled<OP, DT, IT, NOUT, kBigTileUnits>(plan, tile_units, local_numel, grid, block, prm, x, out, mask, stream);
+        return launch_tiled<OP, DT, IT, NOUT, kBigTileUnits>(plan, tile_units, local_numel, grid, block, prm, x, out, mask,
+                                                             stream);
       break;
     case kRagged:
       return enqueue(ragged_kernel<OP, DT, IT, NOUT>, grid, block, stream, plan, prm, x, out, mask);

@@ -301,11 +301,11 @@ extern "C" vesrng_status vesrng_bench_probe(vesrng_probe_kind kind, uint64_t uni
     case VESRNG_PROBE_DROPOUT_TRAFFIC_6_WAVES:
       if (!in || !out2) return VESRNG_ERR_NULL;
       if (kind == VESRNG_PROBE_DROPOUT_TRAFFIC_7_WAVES)
-        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 7>), grid, block, 21u * 1024u, stream, i, o, static_cast<u32x2*>(out2),
-                           units);
+        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 7>), grid, block, 21u * 1024u, stream, i, o,
+                           static_cast<u32x2*>(out2), units);
       else
-        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 6>), grid, block, 26u * 1024u, stream, i, o, static_cast<u32x2*>(out2),
-                           units);
+        hipLaunchKernelGGL((dropout_traffic_probe<kStream, 6>), grid, block, 26u * 1024u, stream, i, o,
+                           static_cast<u32x2*>(out2), units);
       break;
     case VESRNG_PROBE_DROPOUT_TRAFFIC_WIDE_MASK:
       if (!in || !out2) return VESRNG_ERR_NULL;
