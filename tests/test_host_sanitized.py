@@ -278,3 +278,42 @@ def test_short_tile_map_at_its_limits(host_check):
             head, _ = check_tiles(host_check, words, offset, unit_elems, 0, position_of, n, [n // 2, n // 3, n - 5])
             assert head["short"] == want_short, (length, lead, row_stride)
             assert head["units_per_run"] == (lead % 4 + length + 3) // 4
+
+
+def test_tile_map_on_random_column_shards(host_check):
+    """Seeded random column shards - row counts, widths, paddings (row strides that are and are not multiples of
+    four), mesh sizes, ranks, unit sizes, both tile sizes: every slot of the probed tiles is written exactly once
+    with its own stream position, whichever form of the map the library takes (both are walked where the short
+    form applies), and the short form is taken exactly when the row stride is a multiple of four."""
+    rng = np.random.default_rng(20240607)
+    done = short = 0
+    while done < 60:
+        rows = int(rng.integers(40, 4000))
+        cols = int(rng.integers(40, 3000))
+        m = int(rng.integers(2, 6))
+        coord = int(rng.integers(0, m))
+        pad = int(rng.choice([0, 0, 1, 2, 3, 4, 8, 13]))
+        chunk = -(-cols // m)
+        start = coord * chunk
+        w = min(chunk, cols - start)
+        if w < 16:
+            continue
+        row_stride = cols + pad
+        offset = 4 * int(rng.integers(0, 1 << 30))
+        unit_elems = int(rng.choice([4, 8]))
+        big = int(rng.integers(0, 2)) if unit_elems == 4 else 0
+        aligned = (start % 4 == 0 and row_stride % 4 == 0 and w % unit_elems == 0)
+        if aligned:
+            continue                      # takes the aligned kernel: no tile map
+        words = sharding_words([rows, cols], [m], [("S", 1)], [coord], stride=[row_stride, 1] if pad else None)
+
+        def position_of(i, w=w, start=start, row_stride=row_stride, offset=offset):
+            return np.uint64(offset + start) + (i // np.uint64(w)) * np.uint64(row_stride) + i % np.uint64(w)
+
+        n = rows * w
+        head, _ = check_tiles(host_check, words, offset, unit_elems, big, position_of, n,
+                              [int(x) for x in rng.integers(0, n, size=3)])
+        assert head["short"] == (row_stride % 4 == 0), (rows, cols, m, coord, pad)
+        short += head["short"]
+        done += 1
+    assert 10 <= short <= 50
