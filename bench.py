@@ -245,10 +245,13 @@ def roofline_block(op, kernel_tag, nbytes, numel, seconds, floor_s, ceil, cus, r
     t = launch floor + max(memory time at the measured ceiling of the kernel's own store / traffic
     form, issue time of its instruction mix); `bound` names the largest of the three terms."""
     mix = KERNEL_MIX[kernel_tag]
-    mem_ceiling = (ceil["dropout_traffic_gb_per_s"] if op == "dropout"
+    units = (numel + mix["unit_elems"] - 1) // mix["unit_elems"]
+    # Masked dropout runs at seven resident waves per SIMD from 2^23 units on, at the hardware's eight below.
+    traffic = "dropout_traffic_gb_per_s" if units >= (1 << 23) else "dropout_traffic_8_waves_gb_per_s"
+    mem_ceiling = (ceil[traffic] if op == "dropout"
                    else ceil["store_unaligned_gb_per_s"] if ragged else ceil["store_only_gb_per_s"])
     t_mem = nbytes / (mem_ceiling * 1e9)
-    t_alu, per_wave = issue_model_seconds(mix, (numel + mix["unit_elems"] - 1) // mix["unit_elems"], ceil, cus)
+    t_alu, per_wave = issue_model_seconds(mix, units, ceil, cus)
     terms = {"launch": floor_s, "hbm" if not ragged else "store-alignment": t_mem, "alu": t_alu}
     bound = max(terms, key=terms.get)
     t_model = floor_s + max(t_mem, t_alu)
