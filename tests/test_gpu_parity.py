@@ -1270,6 +1270,43 @@ def test_column_shards_whose_runs_share_one_phase():
             assert_float_bits_equal(y, yo, "dropout %s %s" % (dtype, args), dtype=dtype)
 
 
+def test_random_column_shards_through_the_staging_kernel():
+    """Seeded random column shards (row counts, widths, row paddings that are and are not multiples of four, mesh
+    sizes, ranks, offsets), sized to take the small tile, the large tile, the short and the general tile map:
+    raw draws, the fp32 uniform fill, randint and bf16 dropout against the oracle."""
+    rng = np.random.default_rng(424242)
+    done = 0
+    while done < 16:
+        rows = int(rng.integers(200, 9000))
+        cols = int(rng.integers(64, 3000))
+        m = int(rng.integers(2, 5))
+        coord = int(rng.integers(0, m))
+        pad = int(rng.choice([0, 0, 1, 3, 4, 8]))
+        if rng.random() < 0.5:
+            pad = (-cols) % 4 + 4 * int(rng.integers(0, 2))     # a row stride that is a multiple of four
+        chunk = -(-cols // m)
+        w = min(chunk, cols - coord * chunk)
+        if w < 16 or ((coord * chunk) % 4 == 0 and (cols + pad) % 4 == 0 and w % 8 == 0):
+            continue
+        args = ([rows, cols], [m], [("S", 1)], [coord]) + (([cols + pad, 1],) if pad else ())
+        seed, offset = int(rng.integers(0, 1 << 62)), 4 * int(rng.integers(0, 1 << 40))
+        n = rows * w
+        say("random column shard %s, %d elements" % (args, n))
+        got = gpu_fill("raw", None, args, seed, offset)
+        assert np.array_equal(got, oracle.raw_u32(args, seed, offset, threads=THREADS)), args
+        got = gpu_fill("uniform", "f32", args, seed, offset, low=-3.0, high=0.5)
+        want = oracle.uniform(args, oracle.F32, -3.0, 0.5, seed, offset, threads=THREADS)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), args
+        got = gpu_fill("randint", None, args, seed, offset, low=10, high=1 << 20)
+        assert np.array_equal(got, oracle.randint(args, 10, 1 << 20, seed, offset, threads=THREADS)), args
+        x = W.bf16_bits_from_f32(W.adversarial_f32(n, seed=done))
+        yo, mo = oracle.dropout(args, oracle.BF16, 0.45, seed, offset, x, threads=THREADS)
+        y, mk = gpu_dropout("bf16", args, 0.45, seed, offset, x)
+        assert np.array_equal(mk, mo), args
+        assert_float_bits_equal(y, yo, "dropout bf16 %s" % (args,))
+        done += 1
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_contiguous_shards_of_any_length(dtype):
     """A shard that is one contiguous run takes the vector kernel whatever its length; the last,
