@@ -298,7 +298,9 @@ LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offse
   if (rs.phases_equal && (pos0 % 4 == 0) &&
       (rs.run_len % V == 0 || (rs.n_runs == 1 && !traits.whole_blocks_only))) {
     c.flavour = kAligned;
-  } else if (rs.run_len >= 16) {
+  } else if (rs.run_len >= 16 && rs.run_len >= traits.tile_min_run_len &&
+             static_cast<uint64_t>(g.local_numel) >= traits.tile_min_elems &&
+             (traits.tile_max_elems == 0 || static_cast<uint64_t>(g.local_numel) < traits.tile_max_elems)) {
     if (traits.big_tileable && static_cast<uint64_t>(g.local_numel) >= traits.big_tile_min_elems) {
       c.tile_units = pick_tile_units(rs.run_len, V, kBigTileUnits, rs.phases_equal);
       if (c.tile_units != 0) c.flavour = kTiledBig;

@@ -94,6 +94,11 @@ struct LaunchTraits {
   bool tileable = false;            // has a staging kernel
   bool big_tileable = false;        // ... and its large-tile form
   uint64_t big_tile_min_elems = 0;  // smallest shard that takes the large tile
+  // Shards the staging kernels serve at all: local element counts in [tile_min_elems, tile_max_elems) (0 = no
+  // upper limit) with runs of at least tile_min_run_len elements; the rest keeps the kernel without staging.
+  uint64_t tile_min_elems = 0;
+  uint64_t tile_max_elems = 0;
+  uint64_t tile_min_run_len = 16;
   bool whole_blocks_only = false;   // the aligned kernel cannot finish a partial last unit (randint)
 };
 struct LaunchChoice {

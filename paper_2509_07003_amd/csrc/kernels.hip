@@ -851,29 +851,44 @@ hipError_t launch_chain(const Geometry& g, uint64_t offset, const OpParams& prm,
 // ---- dispatch --------------------------------------------------------------------
 // Which kernel a shard takes is decided on the host by choose_launch (geometry.cpp); the traits
 // below say what each operator can use.
-// Operators that take the tiled kernel on ragged shards.  Measured on column shards: staging
-// through LDS doubles the rate of bf16 dropout (5.8 vs 2.4 TB/s) and helps the raw fill
-// (5.4 vs 4.3), the fp32 uniform fill (5.1 vs 4.2) and randint.  The 16-bit fills lose (3.0 vs
-// 3.5) and keep the ragged kernel.
+// Which ragged shards take the staging kernel, operator by operator (measured on column shards of 0.7 M to 358 M
+// elements with runs of 100 to 3414 elements, GPU-side time per launch in graph replays):
+//  * raw, randint, fused dropout, fp32 uniform: every shard with runs of 16 elements and more.  Staging doubles the rate
+//    of bf16 dropout (5.9 vs 2.4 TB/s) and lifts the raw fill from 4.8 to 6.1-6.7 and the fp32 uniform fill to 5.9-6.3.
+//  * fp32 normal: shards below 2^24 elements (10-20 % less time from 0.7 M to 11 M elements - C2's 5.6 M: 7.3 -> 6.0 us -,
+//    level from 22 M on, where the kernel without staging stays: both are bound by instruction issue there).
+//  * 16-bit uniform and normal: shards of 2^21 .. 2^25 elements with runs of 256 elements and more (5-26 % less time;
+//    below, the launch is too small to matter and staging costs a barrier; above, two generator blocks per 16 bytes
+//    make both forms issue-bound and the kernel without staging is 3-10 % ahead; short runs lose up to 10 %).
 #if VESRNG_TILING == -1
 template <int OP, int DT>
-constexpr bool kTileable =
-    (OP == kOpRaw || OP == kOpRandint || kIsDropout<OP> || (OP == kOpUniform && DT == kF32));
+constexpr bool kTileable = true;
+template <int OP, int DT>
+constexpr uint64_t kTileMinElems = ((OP == kOpUniform || OP == kOpNormal) && DT != kF32) ? (1ull << 21) : 0;
+template <int OP, int DT>
+constexpr uint64_t kTileMaxElems = (OP == kOpNormal && DT == kF32)                          ? (1ull << 24)
+                                   : ((OP == kOpUniform || OP == kOpNormal) && DT != kF32) ? (1ull << 25)
+                                                                                            : 0;  // 0: no upper limit
+template <int OP, int DT>
+constexpr uint64_t kTileMinRunLen = ((OP == kOpUniform || OP == kOpNormal) && DT != kF32) ? 256 : 16;
 #else
 template <int OP, int DT>
 constexpr bool kTileable = (VESRNG_TILING != 0);
+template <int OP, int DT>
+constexpr uint64_t kTileMinElems = 0;
+template <int OP, int DT>
+constexpr uint64_t kTileMaxElems = 0;
+template <int OP, int DT>
+constexpr uint64_t kTileMinRunLen = 16;
 #endif
-// Staged through LDS, the raw and fp32 uniform fills gain from four units per thread on all but small
-// shards (measured on column shards of 5.6 M to 358 M elements, short tile map: raw 3.7-5.3 -> 4.0-6.6 TB/s,
-// uniform 3.6-5.1 -> 3.9-6.3); on small shards the four times fewer workgroups no longer fill the chip.
-// The fp32 normal fill is bound by instruction issue: the large tile and no staging at all come out
-// within a few percent of each other at every size (4.4-5.3 TB/s either way, which one leads changes
-// with the run length), the small tile 10-20 % behind; it keeps the kernel without staging.  Dropout
-// and randint, which issue more memory instructions per unit, lose with the large tile and keep one unit.
+// Four aligned units per thread in the store stage (a four times larger tile): the fills of 4-byte elements gain from
+// it on all but small shards (measured with the short tile map: raw 3.7-5.3 -> 4.0-6.6 TB/s, fp32 uniform 3.6-5.1 ->
+// 3.9-6.3, fp32 normal 6.4 -> 6.1 us on C2's shard); on small shards the four times fewer workgroups no longer fill
+// the chip.  Dropout and randint, which issue more memory instructions per unit, lose with the large tile and keep
+// one unit; the 16-bit fills have no large form (their unit is already two generator blocks).
 template <int OP, int DT>
 constexpr bool kBigTileable = (VESRNG_TILING == -1 || VESRNG_TILING == 2) &&
-                              ((OP == kOpRaw || OP == kOpUniform || (OP == kOpNormal && VESRNG_TILING == 2)) &&
-                               UnitOf<OP, DT>::kElems == 4);
+                              ((OP == kOpRaw || OP == kOpUniform || OP == kOpNormal) && UnitOf<OP, DT>::kElems == 4);
 // Smallest shard that takes the big tile (measured: level at 2.8 M elements, 6 % ahead at 5.6 M).
 #ifdef VESRNG_BIG_TILE_MIN_ELEMS  // measurement variants only: force one tile size
 template <int OP>
@@ -969,6 +984,9 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   traits.tileable = kTileable<OP, DT>;
   traits.big_tileable = kBigTileable<OP, DT>;
   traits.big_tile_min_elems = kBigTileMinElems<OP>;
+  traits.tile_min_elems = kTileMinElems<OP, DT>;
+  traits.tile_max_elems = kTileMaxElems<OP, DT>;
+  traits.tile_min_run_len = kTileMinRunLen<OP, DT>;
   traits.whole_blocks_only = (OP == kOpRandint);
   const LaunchChoice c = choose_launch(g, rs, offset, traits);
   if (c.wide)

@@ -13,7 +13,8 @@
 //       -> "G status ndim local_shape[ndim] numel" and, when status == 0 and numel <= max_print,
 //          " J j(0) .. j(numel-1)" from vesrng_global_index and " K ..." from
 //          vesrng_global_index_general; then " A status new_offset" of vesrng_advance_offset(0).
-//   T sharding offset unit_elems tileable big_tileable big_min_elems whole_blocks_only ntiles tile[ntiles]
+//   T sharding offset unit_elems tileable big_tileable big_min_elems whole_blocks_only tile_min_elems tile_max_elems
+//     tile_min_run_len ntiles tile[ntiles]
 //       -> "T status flavour wide units_per_run tile_units n_tiles_total short=0|1" (short: the short form of the
 //          tile map applies and was walked next to the general one) and per requested tile
 //          " | i0 lim count dummy_writes pos(0) .. pos(lim-1)": the stream position whose value
@@ -184,7 +185,8 @@ void tile_request(std::istringstream& in) {
   LaunchTraits traits;
   int tileable = 0, big = 0, whole = 0;
   if (!read_sharding(in, d) ||
-      !(in >> offset >> traits.unit_elems >> tileable >> big >> traits.big_tile_min_elems >> whole >> ntiles)) {
+      !(in >> offset >> traits.unit_elems >> tileable >> big >> traits.big_tile_min_elems >> whole >> traits.tile_min_elems >>
+        traits.tile_max_elems >> traits.tile_min_run_len >> ntiles)) {
     std::printf("T parse-error\n");
     return;
   }

@@ -1066,6 +1066,30 @@ def test_f16_fills_all_kernel_flavours():
     assert e.value.status == 8
 
 
+def test_staged_normal_and_sixteen_bit_fills_on_mid_sized_ragged_shards():
+    """The fp32 normal fill below 2^24 elements and the 16-bit uniform and normal fills of 2^21 .. 2^25 elements (runs
+    of 256 and more) take the staging kernel on ragged shards; just outside those windows they take the kernel without
+    staging.  Both sides of every limit against the oracle, with the short and the general form of the tile map."""
+    seed, offset = 13579, 1 << 33
+    inside = [([2048, 4096], [3], [("S", 1)], [1]),          # 2.8 M elements, runs of 1366, one phase
+              ([2100, 4101], [3], [("S", 1)], [2]),          # 2.9 M, runs of 1367, rotating phases
+              ([9000, 1028], [2], [("S", 1)], [1], [1030, 1])]  # 4.6 M, padded rows (stride not a multiple of four)
+    outside = [([1500, 4096], [3], [("S", 1)], [1]),         # 2.0 M: below the 16-bit window
+               ([12000, 600], [3], [("S", 1)], [1]),         # 2.4 M but runs of 200: too short for the 16-bit fills
+               ([2 ** 14, 4100], [3], [("S", 1)], [1])]      # 22 M: above the fp32 normal window, inside the 16-bit one
+    for args in inside + outside:
+        say("staged fills %s" % (args,))
+        for dtype, code in (("bf16", oracle.BF16), ("f16", oracle.F16)):
+            got = gpu_fill("uniform", dtype, args, seed, offset, low=-1.0, high=1.0)
+            want = oracle.uniform(args, code, -1.0, 1.0, seed, offset, threads=THREADS)
+            assert np.array_equal(got, want), (args, dtype)
+            got = gpu_fill("normal", dtype, args, seed, offset, mean=0.5, std=2.0)
+            check_normal(got, args, dtype, 0.5, 2.0, seed, offset, "normal %s %s" % (dtype, args))
+        got = gpu_fill("normal", "f32", args, seed, offset, mean=-1.0, std=0.5)
+        check_normal(got, args, "f32", -1.0, 0.5, seed, offset, "normal f32 %s" % (args,))
+        del got, want
+
+
 def test_f16_dropout_and_residual_add_all_kernel_flavours():
     seed, offset = 2025, 64
     for k, args in enumerate(F16_CASES):

@@ -189,9 +189,11 @@ def parse_t(line):
 TILED, TILED_BIG = 1, 2
 
 
-def tile_request(words, offset, unit_elems, tileable, big, big_min, whole, tiles):
-    return "T %s %d %d %d %d %d %d %d %s" % (words, offset, unit_elems, tileable, big, big_min, whole, len(tiles),
-                                             " ".join(str(t) for t in tiles))
+def tile_request(words, offset, unit_elems, tileable, big, big_min, whole, tiles, limits=(0, 0, 16)):
+    """limits: the staging kernels serve element counts in [limits[0], limits[1]) (0 = no upper limit) with runs of
+    at least limits[2] elements."""
+    return "T %s %d %d %d %d %d %d %d %d %d %d %s" % ((words, offset, unit_elems, tileable, big, big_min, whole) + tuple(limits)
+                                                      + (len(tiles), " ".join(str(t) for t in tiles)))
 
 
 def check_tiles(host_check, words, offset, unit_elems, big, position_of, local_numel, probe_elements, threads_units=256):
@@ -317,3 +319,19 @@ def test_tile_map_on_random_column_shards(host_check):
         short += head["short"]
         done += 1
     assert 10 <= short <= 50
+
+
+def test_staging_limits_of_an_operator(host_check):
+    """An operator may leave shards outside an element-count window, or with short runs, to the kernel without
+    staging (the fp32 normal fill above 2^24 elements; the 16-bit fills outside 2^21 .. 2^25 or with runs under 256)."""
+    RAGGED = 3
+    for rows, cols, limits, want in ((4096, 4096, (0, 1 << 24, 16), TILED_BIG),          # 5.6 M elements: inside
+                                     (16384, 4096, (0, 1 << 24, 16), RAGGED),            # 22 M: beyond the window
+                                     (1024, 4096, (0, 1 << 24, 16), TILED),              # 1.4 M: small tile
+                                     (1024, 4096, (1 << 21, 1 << 25, 256), RAGGED),      # below the window
+                                     (2048, 4096, (1 << 21, 1 << 25, 256), TILED),       # 2.8 M, runs of 1366
+                                     (30000, 303, (1 << 21, 1 << 25, 256), RAGGED),      # 3 M, runs of 101: too short
+                                     (30000, 303, (0, 0, 16), TILED)):
+        words = sharding_words([rows, cols], [3], [("S", 1)], [1])
+        head = parse_t(host_check([tile_request(words, 0, 4, 1, 1, 1 << 22, 0, [], limits)])[0])
+        assert head["flavour"] == want, (rows, cols, limits)
