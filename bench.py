@@ -33,11 +33,13 @@ SETTLE_SECONDS = 0.25        # untimed launches before any timed region: the fir
                              # work after an idle period run slower (clocks ramp up)
 
 # Vector-ALU instructions per wavefront of the kernels the workload configs run, by issue class.
-# Each lane of a wave produces one unit (4 fp32 or 8 bf16 elements).  Counts are those of the
-# compiler's listing of the kernel (hipcc -S), which for these straight-line kernels is what the
-# hardware counter SQ_INSTS_VALU / SQ_WAVES reads (profiles/counters_bench_kernels.txt);
-# tests/test_bench_model.py recounts them from a fresh listing.  "other" = everything that is
-# neither a Philox product (v_mad_u64_u32), a Philox XOR (v_bitop3_b32) nor a transcendental.
+# Each lane of a wave produces one unit (4 fp32 or 8 bf16 elements; the staging kernel with the large
+# tile: four units, "loop_iterations" passes of its generator loop).  Counts are those of the
+# compiler's listing of the kernel (hipcc -S), which for the straight-line kernels is what the
+# hardware counter SQ_INSTS_VALU / SQ_WAVES reads (profiles/counters_bench_kernels.txt); for the
+# staging kernel the generator classes are the listing's loop body times the passes and the total is
+# the counter's.  tests/test_bench_model.py recounts them from a fresh listing.  "other" = everything that
+# is neither a Philox product (v_mad_u64_u32), a Philox XOR (v_bitop3_b32) nor a transcendental.
 KERNEL_MIX = {
     "aligned normal bf16": {"kernel": "aligned_kernel<2, 1, unsigned int, 1, true>", "unit_elems": 8,
                             "mad_u64_u32": 38, "bitop3_b32": 40, "trans": 16, "other": 56},
@@ -49,6 +51,8 @@ KERNEL_MIX = {
                             "mad_u64_u32": 19, "bitop3_b32": 20, "trans": 0, "other": 24},
     "ragged normal f32": {"kernel": "ragged_kernel<2, 0, unsigned int, 1>", "unit_elems": 4,
                           "mad_u64_u32": 22, "bitop3_b32": 20, "trans": 8, "other": 50},
+    "staged normal f32": {"kernel": "tiled_kernel<2, 0, unsigned int, 1, 4, 2>", "unit_elems": 16, "loop_iterations": 4,
+                          "mad_u64_u32": 80, "bitop3_b32": 80, "trans": 32, "other": 213},
 }
 SIMPLE_CLASSES = ["add_u32", "fma_f32", "mul_f32", "cvt_f32_u32", "cvt_pk_bf16_f32", "lshrrev_b32", "mul_lo_u32",
                   "cmp_cndmask_b32"]
@@ -268,8 +272,9 @@ def roofline_block(op, kernel_tag, nbytes, numel, seconds, floor_s, ceil, cus, r
 
 def steady_state(v, W, torch, ceil, cus):
     """The operators of the small configs at 64x the shard (same shapes of run), where launch latency
-    no longer dominates: C2's ragged fp32 normal fill and C3's bf16 normal fill (their own kernels), each
-    against its measured ceilings; and the virtual-thread layout on an unsharded tensor."""
+    no longer dominates: C2's ragged fp32 normal fill (at this size the kernel without staging; C2 itself,
+    below 2^24 elements, is staged) and C3's bf16 normal fill, each against its measured ceilings; and the
+    virtual-thread layout on an unsharded tensor."""
     import copy
     res = {}
     for wl, tag, ragged in ((W.C2, "ragged normal f32", True), (W.C3, "aligned normal bf16", False)):
@@ -467,23 +472,53 @@ def design_choices(v, B, W, torch, once=False):
             ms = sorted(time_graph(torch, launch, 4 * copies) for _ in range(3))[1]
             rows[label] = {"us_per_launch": ms * 1e3, "gb_per_s": nb / (ms * 1e-3) / 1e9, "launches_per_burst": 4 * copies}
         res["%s (graph replay): argument-fetch pinning" % wl.name.split()[0]] = {"choice": "pinned", "measured": rows}
-    # Ragged column shards [rows, 4096] cut three ways (C2's shape of run), two sizes.
-    for rows in (16384, 98304):
+    # Ragged column shards [rows, 4096] cut three ways (C2's shape of run): C2 itself and two larger sizes.  C2's own
+    # shard takes a few microseconds: it is timed as the per-config blocks time it, GPU-side from a HIP-graph replay
+    # over buffers that together exceed the last-level cache.
+    def entry_graph(name, choice, cases, copies):
+        rows = {}
+        for label, fn, nbytes in cases:
+            if once:
+                for k in range(3):
+                    fn(k)
+                torch.cuda.synchronize()
+                rows[label] = {"launches": 3}
+                continue
+            ms = sorted(time_graph(torch, fn, 4 * copies) for _ in range(3))[1]
+            rows[label] = {"us_per_launch": ms * 1e3, "gb_per_s": nbytes / (ms * 1e-3) / 1e9, "launches_per_burst": 4 * copies}
+        res[name + " (graph replay)"] = {"choice": choice, "measured": rows}
+
+    for rows in (4096, 16384, 98304):
         shr = v.Sharding([rows, 4096], [3], [("S", 1)], [1])
         nr = v.vesrng_local_shape(shr)[1]
-        oi = o[:nr].view(torch.int32)
-        of = o[:nr]
-        for op, call in (("raw", lambda L: (lambda: L.vesrng_raw_u32(shr, 1, 0, oi))),
-                         ("fp32 uniform", lambda L: (lambda: L.vesrng_uniform(shr, v.F32, 0.0, 1.0, 1, 0, of))),
-                         ("fp32 normal", lambda L: (lambda: L.vesrng_normal(shr, v.F32, 0.0, 1.0, 1, 0, of)))):
-            entry("ragged %s fill, %d elements" % (op, nr), "large tile for raw and uniform from 2^22 elements, no staging for normal",
-                  [("library (kept)", call(v), 4 * nr),
-                   ("no staging, element-aligned stores", call(variants["ragged"]), 4 * nr),
-                   ("no staging, realigned across lanes (DPP)", call(variants["realign"]), 4 * nr),
-                   ("staged, small tile", call(variants["smalltile"]), 4 * nr),
-                   ("staged, large tile", call(variants["bigtile"]), 4 * nr),
-                   ("library's choice with the tile map per wavefront (scalar)", call(variants["wavetile"]), 4 * nr),
-                   ("library's choice with the general form of the tile map", call(variants["longmap"]), 4 * nr)])
+        copies = 32 if rows == 4096 else 1
+        ofs = [o[k * nr:(k + 1) * nr] for k in range(copies)]
+        ois = [t.view(torch.int32) for t in ofs]
+        obs = [t.view(torch.bfloat16)[:nr] for t in ofs]
+        for op, call, bpe in (("raw", lambda L: (lambda k=0: L.vesrng_raw_u32(shr, 1, 0, ois[k % copies])), 4),
+                              ("fp32 uniform", lambda L: (lambda k=0: L.vesrng_uniform(shr, v.F32, 0.0, 1.0, 1, 0, ofs[k % copies])), 4),
+                              ("fp32 normal", lambda L: (lambda k=0: L.vesrng_normal(shr, v.F32, 0.0, 1.0, 1, 0, ofs[k % copies])), 4),
+                              ("bf16 uniform", lambda L: (lambda k=0: L.vesrng_uniform(shr, v.BF16, 0.0, 1.0, 1, 0, obs[k % copies])), 2)):
+            if bpe == 2:
+                name, choice = ("ragged %s fill, %d elements" % (op, nr),
+                                "staged (small tile) from 2^21 to 2^25 elements with runs of 256 and more, else no staging")
+                cases = [("library (kept)", call(v), 2 * nr), ("no staging", call(variants["ragged"]), 2 * nr),
+                         ("staged, small tile", call(variants["smalltile"]), 2 * nr)]
+            else:
+                name, choice = ("ragged %s fill, %d elements" % (op, nr),
+                                "raw and uniform: small tile below 2^22 elements, large tile from there; "
+                                "normal: the same below 2^24 elements, no staging above")
+                cases = [("library (kept)", call(v), 4 * nr),
+                         ("no staging, element-aligned stores", call(variants["ragged"]), 4 * nr),
+                         ("no staging, realigned across lanes (DPP)", call(variants["realign"]), 4 * nr),
+                         ("staged, small tile", call(variants["smalltile"]), 4 * nr),
+                         ("staged, large tile", call(variants["bigtile"]), 4 * nr),
+                         ("library's choice with the tile map per wavefront (scalar)", call(variants["wavetile"]), 4 * nr),
+                         ("library's choice with the general form of the tile map", call(variants["longmap"]), 4 * nr)]
+            if copies > 1:
+                entry_graph(name, choice, cases, copies)
+            else:
+                entry(name, choice, cases)
         # Fused bf16 dropout on the same shard (small tile): 5 bytes per element.
         xr = torch.randn(nr, dtype=torch.float32, device="cuda").to(torch.bfloat16)
         orr = torch.empty_like(xr)
@@ -615,7 +650,7 @@ def main():
         floor_ms = time_graph(torch, lambda k: v.vesrng_uniform(tiny, v.F32, 0.0, 1.0, 1, 0, tbuf), 64)
         ceil["launch_floor_us"] = floor_ms * 1e3
         extra = {}
-        tags = {"C1": ("aligned uniform f32", False), "C2": ("ragged normal f32", True), "C3": ("aligned normal bf16", False),
+        tags = {"C1": ("aligned uniform f32", False), "C2": ("staged normal f32", False), "C3": ("aligned normal bf16", False),
                 "C4": ("aligned dropout bf16", False), "C5i": ("aligned dropout bf16", False)}
         for wl, copies in ((W.C1, 256), (W.C2, 16), (W.C3, 32), (W.C4, 8), (W.C5_INTERLEAVED, 1)):
             key = wl.name.split()[0] + ("i" if wl is W.C5_INTERLEAVED else "")

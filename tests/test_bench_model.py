@@ -52,11 +52,16 @@ def test_instruction_mix_table_matches_the_compiler_listing(listing):
         h = histogram(listing, mangled(mix["kernel"]))
         valu = sum(c for m, c in h.items() if m.startswith("v_"))
         trans = sum(c for m, c in h.items() if re.match(r"v_(log|sqrt|sin|cos|exp|rcp|rsq)_f32", m))
-        assert h["v_mad_u64_u32"] == mix["mad_u64_u32"], tag
-        assert h["v_bitop3_b32"] == mix["bitop3_b32"], tag
-        assert trans == mix["trans"], tag
+        passes = mix.get("loop_iterations", 1)   # the staging kernel's generator loop runs this often per wave
+        assert h["v_mad_u64_u32"] * passes == mix["mad_u64_u32"], tag
+        assert h["v_bitop3_b32"] * passes == mix["bitop3_b32"], tag
+        assert trans * passes == mix["trans"], tag
         total = mix["mad_u64_u32"] + mix["bitop3_b32"] + mix["trans"] + mix["other"]
-        if tag in straight_line:
+        if passes > 1:
+            # A loop: the per-wave total is the hardware counter's (checked against the committed profile below);
+            # it must at least cover the generator classes and stay under `passes` times the whole listing.
+            assert mix["other"] > 0 and total < passes * valu, (tag, valu, total)
+        elif tag in straight_line:
             assert valu == total, (tag, valu, total)          # no branches: the listing is what a wave executes
         else:
             # Branchy kernels (a wave-uniform choice between two conversions; edge paths): a wave executes
