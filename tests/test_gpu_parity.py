@@ -1238,8 +1238,8 @@ def test_generator_sequence_of_operators_matches_one_device_doing_the_same_seque
 
 def test_large_ragged_fp32_fills():
     """Ragged column shards big enough (2^22 elements and more) to take the large-tile form of the staging
-    kernel - raw and uniform fp32 - and the fp32 normal fill, which stays on the kernel without staging at
-    every size, against the threaded oracle, with the rows' phases equal (row length 4100) and unequal (4101)."""
+    kernel - raw and uniform fp32 - and the fp32 normal fill on a shard of 2^26 elements, where it takes the kernel
+    without staging, against the threaded oracle, with the rows' phases equal (row length 4100) and unequal (4101)."""
     seed, offset = 31337, 1 << 33
     for cols in (4100, 4101):
         args = ([16384, cols], [3], [("S", 1)], [1])
