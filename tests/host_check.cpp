@@ -222,6 +222,25 @@ void tile_request(std::istringstream& in) {
 
 }  // namespace
 
+// "D d n(0) n(1) ..." -> "D q64(0) q64(1) ... | q32 ..." : the kernels' divisions by the launch constant d (64-bit form on
+// every n; the multiply-shift 32-bit form on the n below 2^31 when d <= 2^31, the range it is specified for).
+void division_request(std::istringstream& in) {
+  uint64_t d = 0, n = 0;
+  in >> d;
+  std::vector<uint64_t> ns;
+  while (in >> n) ns.push_back(n);
+  const Div64 wide = DivOf<uint64_t>::make(d);
+  std::printf("D");
+  for (uint64_t x : ns) std::printf(" %llu", static_cast<unsigned long long>(wide.div(x)));
+  std::printf(" |");
+  if (d <= (1ull << 31)) {
+    const Div32 narrow = DivOf<uint32_t>::make(d);
+    for (uint64_t x : ns)
+      if (x < (1ull << 31)) std::printf(" %u", narrow.div(static_cast<uint32_t>(x)));
+  }
+  std::printf("\n");
+}
+
 int main() {
   std::string line;
   while (std::getline(std::cin, line)) {
@@ -229,6 +248,7 @@ int main() {
     std::istringstream in(line.substr(1));
     if (line[0] == 'G') geometry_request(in);
     else if (line[0] == 'T') tile_request(in);
+    else if (line[0] == 'D') division_request(in);
     else std::printf("? unknown request\n");
   }
   return 0;

@@ -335,3 +335,31 @@ def test_staging_limits_of_an_operator(host_check):
         words = sharding_words([rows, cols], [3], [("S", 1)], [1])
         head = parse_t(host_check([tile_request(words, 0, 4, 1, 1, 1 << 22, 0, [], limits)])[0])
         assert head["flavour"] == want, (rows, cols, limits)
+
+
+def test_divisions_by_launch_constants_against_exact_integers(host_check):
+    """The kernels divide by launch constants: with a high multiply and a shift where dividends stay below 2^31
+    (plan.h: Div32), by the compiler's division on the 64-bit index path (Div64).  Divisors of every size class - 1, powers of two and their neighbours,
+    the largest values, random ones - against Python's integers on dividends that sit on and next to multiples of
+    the divisor, at the ends of the range, and at random."""
+    rng = np.random.default_rng(64)
+    divisors = [1, 2, 3, 5, 7, 10, 255, 256, 257, 1366, 4096, 65535, 65536, 65537, 2 ** 31 - 1, 2 ** 31, 2 ** 31 + 1,
+                2 ** 32 - 1, 2 ** 32, 2 ** 32 + 1, 2 ** 33 + 5, 2 ** 40 - 87, 2 ** 62, 2 ** 63 - 1, 2 ** 63, 2 ** 63 + 1,
+                2 ** 64 - 2, 2 ** 64 - 1]
+    divisors += [int(x) for x in rng.integers(1, 2 ** 20, size=40)] + [int(x) for x in rng.integers(1, 2 ** 62, size=40)]
+    divisors += [int(rng.integers(1, 2 ** 32)) * int(rng.integers(1, 2 ** 31)) for _ in range(20)]
+    lines, cases = [], []
+    for d in divisors:
+        ns = {0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, 2 ** 31 - 1, 2 ** 31, 2 ** 32 - 1, 2 ** 32, 2 ** 63 - 1, 2 ** 63,
+              2 ** 64 - 1, 2 ** 64 - 2, (2 ** 64 - 1) // d * d, (2 ** 64 - 1) // d * d - 1}
+        ns |= {int(k) * d + int(r) for k, r in zip(rng.integers(0, max(1, (2 ** 64 - 1) // d), size=24, dtype=np.uint64),
+                                                   rng.integers(0, min(d, 2 ** 62), size=24))}
+        ns |= {int(x) for x in rng.integers(0, 2 ** 63, size=16)} | {int(x) for x in rng.integers(0, 2 ** 31, size=16)}
+        ns = sorted(x for x in ns if 0 <= x < 2 ** 64)
+        lines.append("D %d %s" % (d, " ".join(str(x) for x in ns)))
+        cases.append((d, ns))
+    for line, (d, ns) in zip(host_check(lines), cases):
+        wide, narrow = line[1:].split("|")
+        assert [int(x) for x in wide.split()] == [x // d for x in ns], d
+        if d <= 2 ** 31:
+            assert [int(x) for x in narrow.split()] == [x // d for x in ns if x < 2 ** 31], d
