@@ -52,6 +52,9 @@ TARGETS = {
     # Fused dropout that writes a mask at the hardware's full eight resident waves per SIMD (no cap at seven).
     "variant_nocap": {"lib": "libvesrng_variant_nocap.so", "sources": PRODUCT_SOURCES,
                       "defines": ["VESRNG_VARIANT_TAG=nocap", "VESRNG_CAP_MASKED_DROPOUT_WAVES=0"]},
+    # Shards of 2^30 elements and more through the 64-bit index kernels as a whole instead of piece by piece.
+    "variant_widekernels": {"lib": "libvesrng_variant_widekernels.so", "sources": PRODUCT_SOURCES,
+                            "defines": ["VESRNG_VARIANT_TAG=widekernels", "VESRNG_WIDE_SHARDS_IN_PIECES=0"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

@@ -318,6 +318,30 @@ LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offse
   return c;
 }
 
+RunShape piece_shape(const RunShape& rs, uint64_t rows) {
+  RunShape piece = rs;
+  const uint64_t extent = static_cast<uint64_t>(rs.outer.back().extent);
+  piece.outer.back().extent = static_cast<int64_t>(rows);
+  piece.n_runs = rs.n_runs / extent * rows;
+  return piece;
+}
+
+bool plan_pieces(const RunShape& rs, uint64_t units_per_run, Pieces* p) {
+  if (rs.outer.empty()) return false;
+  const Axis top = rs.outer.back();
+  p->extent = static_cast<uint64_t>(top.extent);
+  p->stride = static_cast<uint64_t>(top.stride);
+  p->per_index = rs.n_runs / p->extent * rs.run_len;
+  // Bounded by elements first (fits_32bit's limit), then checked in full: units per run exceed elements per run
+  // only for runs shorter than a unit, which the second test catches.
+  uint64_t rows = ((1ull << 30) - 1) / p->per_index;
+  rows -= rows % 32;
+  while (rows >= 32 && !fits_32bit(piece_shape(rs, rows), units_per_run)) rows -= 32;
+  if (rows < 32) return false;
+  p->rows_per_piece = rows;
+  return true;
+}
+
 bool plan_theta(const Geometry& g, const RunShape& rs, uint64_t offset, uint64_t unit_elems, ThetaPlan* tp) {
   const uint64_t theta = g.virtual_threads, n = static_cast<uint64_t>(g.local_numel), V = unit_elems;
   if (theta == 0 || !g.boxed || n == 0) return false;

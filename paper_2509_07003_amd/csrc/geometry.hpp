@@ -109,6 +109,25 @@ struct LaunchChoice {
 };
 LaunchChoice choose_launch(const Geometry& g, const RunShape& rs, uint64_t offset, const LaunchTraits& traits);
 
+// ---- shards whose indices need 64 bits, cut into pieces that do not -----------------
+// A shard of 2^30 elements and more takes the 64-bit index instantiation of the kernels, whose index arithmetic
+// costs the instruction-bound operators up to a third of their rate.  When the shard has at least one axis of
+// runs it can instead be served piece by piece: the outermost axis of runs is the slowest local dimension, so
+// `rows` consecutive indices of it are a contiguous part of the local tensor and a shard of the same kind
+// (same run length, strides, phases), `rows` times `per_index` elements long, whose first element sits `stride`
+// stream positions per index further on.  rows_per_piece is a multiple of 32, so that every piece starts on a
+// 128-byte line of every buffer whatever the element size.
+struct Pieces {
+  uint64_t rows_per_piece = 0;  // indices of the outermost run axis per piece (the last piece may be shorter)
+  uint64_t per_index = 0;       // local elements per index of that axis
+  uint64_t extent = 0;          // extent of that axis
+  uint64_t stride = 0;          // its global stride, in elements
+};
+// Fills `p` and returns true when the shard can be cut so that every piece fits the 32-bit index path.
+bool plan_pieces(const RunShape& rs, uint64_t units_per_run, Pieces* p);
+// The run shape of `rows` indices of the outermost run axis.
+RunShape piece_shape(const RunShape& rs, uint64_t rows);
+
 // ---- the virtual-thread layout with one generator call per four outputs ------------
 // Algorithm 1's (tau, beta) virtualisation puts element j at virtual thread tau = j mod Theta,
 // step s = j / Theta; word s mod 4 of block (offset / 4 + s / 4, tau).  The four words of one

@@ -71,6 +71,11 @@
 #ifndef VESRNG_CAP_MASKED_DROPOUT_WAVES
 #define VESRNG_CAP_MASKED_DROPOUT_WAVES 1
 #endif
+// 1 (always, in the library): shards that need 64-bit indices as a whole are served piece by piece through the 32-bit
+// kernels where they can be cut.  0 only in the measurement variant that times the 64-bit kernels on them.
+#ifndef VESRNG_WIDE_SHARDS_IN_PIECES
+#define VESRNG_WIDE_SHARDS_IN_PIECES 1
+#endif
 #ifndef VESRNG_TILE_SAME_PHASE
 #define VESRNG_TILE_SAME_PHASE 1
 #endif
@@ -952,12 +957,12 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
   return hipErrorInvalidValue;
 }
 
+// `n`: local elements the launch covers (the whole shard, or one piece of it).
 template <int OP, int DT, typename IT>
-hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, uint64_t offset,
+hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, uint64_t n, uint64_t offset,
                         uint64_t units_per_run, uint64_t tile_units, const OpParams& prm, const void* x, void* out,
                         uint8_t* mask, hipStream_t stream) {
   const PlanT<IT> plan = make_plan<IT>(g, rs, offset, units_per_run);
-  const uint64_t n = static_cast<uint64_t>(g.local_numel);
   switch (plan.n_outer) {
     case 0: return launch_nout<OP, DT, IT, 0>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
     case 1: return launch_nout<OP, DT, IT, 1>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
@@ -989,9 +994,29 @@ hipError_t launch_dt(const Geometry& g, uint64_t offset, const OpParams& prm, co
   traits.tile_min_run_len = kTileMinRunLen<OP, DT>;
   traits.whole_blocks_only = (OP == kOpRandint);
   const LaunchChoice c = choose_launch(g, rs, offset, traits);
-  if (c.wide)
-    return launch_typed<OP, DT, uint64_t>(c.flavour, g, rs, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
-  return launch_typed<OP, DT, uint32_t>(c.flavour, g, rs, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
+  const uint64_t n = static_cast<uint64_t>(g.local_numel);
+  if (!c.wide)
+    return launch_typed<OP, DT, uint32_t>(c.flavour, g, rs, n, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
+  // A shard that needs 64-bit indices as a whole: piece by piece through the 32-bit kernels where it can be cut
+  // (geometry.hpp: Pieces), one launch per piece, each on its own part of every buffer.
+  Pieces pc;
+  if (VESRNG_WIDE_SHARDS_IN_PIECES != 0 && plan_pieces(rs, c.units_per_run, &pc)) {
+    constexpr uint64_t out_bytes = (OP == kOpRandint) ? 8 : (OP == kOpRaw || DT == kF32) ? 4 : 2;
+    constexpr uint64_t x_bytes = (DT == kF32) ? 4 : 2;
+    for (uint64_t row = 0; row < pc.extent; row += pc.rows_per_piece) {
+      const uint64_t rows = (pc.extent - row < pc.rows_per_piece) ? pc.extent - row : pc.rows_per_piece;
+      const uint64_t first = row * pc.per_index;  // first local element of the piece
+      OpParams piece_prm = prm;
+      if (prm.residual) piece_prm.residual = static_cast<const char*>(prm.residual) + first * x_bytes;
+      const hipError_t e = launch_typed<OP, DT, uint32_t>(
+          c.flavour, g, piece_shape(rs, rows), rows * pc.per_index, offset + row * pc.stride, c.units_per_run, c.tile_units,
+          piece_prm, x ? static_cast<const char*>(x) + first * x_bytes : nullptr, static_cast<char*>(out) + first * out_bytes,
+          mask ? mask + first : nullptr, stream);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  return launch_typed<OP, DT, uint64_t>(c.flavour, g, rs, n, offset, c.units_per_run, c.tile_units, prm, x, out, mask, stream);
 }
 
 // The floating-point operators, by output dtype.

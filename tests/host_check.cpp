@@ -241,6 +241,37 @@ void division_request(std::istringstream& in) {
   std::printf("\n");
 }
 
+// "P sharding offset unit_elems" -> "P wide cut rows_per_piece per_index extent stride pieces_fit": how the library cuts a
+// shard that needs 64-bit indices into pieces for the 32-bit kernels (cut = 0: it cannot, the 64-bit kernels serve it).
+void pieces_request(std::istringstream& in) {
+  Desc d;
+  uint64_t offset = 0;
+  LaunchTraits traits;
+  if (!read_sharding(in, d) || !(in >> offset >> traits.unit_elems)) {
+    std::printf("P parse-error\n");
+    return;
+  }
+  traits.tileable = traits.big_tileable = true;
+  Geometry g;
+  if (build_geometry(&d.s, &g) != VESRNG_OK || !g.boxed || g.local_numel == 0) {
+    std::printf("P not-a-box-or-empty\n");
+    return;
+  }
+  const RunShape rs = run_shape(g);
+  const LaunchChoice c = choose_launch(g, rs, offset, traits);
+  Pieces pc;
+  const bool cut = plan_pieces(rs, c.units_per_run, &pc);
+  int fit = 1;
+  if (cut) {
+    const uint64_t last = pc.extent % pc.rows_per_piece;
+    fit = fits_32bit(piece_shape(rs, pc.rows_per_piece), c.units_per_run) &&
+          (last == 0 || fits_32bit(piece_shape(rs, last), c.units_per_run));
+  }
+  std::printf("P %d %d %llu %llu %llu %llu %d\n", c.wide ? 1 : 0, cut ? 1 : 0, static_cast<unsigned long long>(pc.rows_per_piece),
+              static_cast<unsigned long long>(pc.per_index), static_cast<unsigned long long>(pc.extent),
+              static_cast<unsigned long long>(pc.stride), fit);
+}
+
 int main() {
   std::string line;
   while (std::getline(std::cin, line)) {
@@ -249,6 +280,7 @@ int main() {
     if (line[0] == 'G') geometry_request(in);
     else if (line[0] == 'T') tile_request(in);
     else if (line[0] == 'D') division_request(in);
+    else if (line[0] == 'P') pieces_request(in);
     else std::printf("? unknown request\n");
   }
   return 0;

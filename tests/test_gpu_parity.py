@@ -1026,6 +1026,112 @@ def test_table5_large_tensors_on_sampled_windows(label, shape):
         del x, y, mask, xh
 
 
+def test_shards_beyond_2_to_30_elements_served_piece_by_piece():
+    """A shard of 2^30 elements and more with an axis of runs is cut along that axis into pieces that the 32-bit
+    kernels serve, one launch each (rows per piece: the largest multiple of 32 whose elements stay below 2^30).
+    Windows around every piece boundary, at both ends and in the middle against the oracle: rows of 50 and of 37
+    elements off the block grid (staged fp32 uniform, randint), rows of 100 aligned elements (bf16 normal, fused
+    bf16 dropout; with residual against a shard that fits 32 bits as a whole), and a shard with rows too long to
+    cut, which keeps the 64-bit kernels."""
+    seed, offset = 77177, 1 << 36
+    width = 6000
+
+    def windows(n, per_index):
+        rows = ((1 << 30) - 1) // per_index
+        rows -= rows % 32
+        marks = [0, n - width, n // 2] + [k * rows * per_index for k in range(1, -(-n // (rows * per_index)))]
+        out = []
+        for mk in marks:
+            b = max(0, min(n - width, mk - width // 2))
+            out.append((b, b + width))
+        return out
+
+    # Rows of 50 elements starting at column 50 (phase 2): ragged, staged; 1.68e9 elements.
+    args = ([1 << 25, 100], [2], [("S", 1)], [1])
+    sh = v.Sharding(*args)
+    n = v.vesrng_local_shape(sh)[1]
+    assert n == 50 << 25
+    say("pieces: ragged rows of 50, %d elements" % n)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    v.vesrng_uniform(sh, v.F32, -1.0, 1.0, seed, offset, out)
+    torch.cuda.synchronize()
+    wins = windows(n, 50)
+    assert len(wins) >= 4
+    for b, e in wins:
+        want = oracle.uniform(args, oracle.F32, -1.0, 1.0, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(out[b:e].cpu().numpy(), want), (b, e)
+    del out
+    args_w = ([1 << 25, 74], [2], [("S", 1)], [1])          # rows of 37 from column 37: 1.24e9 elements, cut in two
+    sh_w = v.Sharding(*args_w)
+    nw = v.vesrng_local_shape(sh_w)[1]
+    outi = torch.empty(nw, dtype=torch.int64, device=DEV)
+    v.vesrng_randint(sh_w, -7, 1 << 31, seed, offset, outi)
+    torch.cuda.synchronize()
+    for b, e in windows(nw, 37):
+        want = oracle.randint(args_w, -7, 1 << 31, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(outi[b:e].cpu().numpy(), want), (b, e)
+    del outi
+
+    # Rows of 100 aligned elements: bf16 normal fill and fused dropout + residual.
+    args = ([1 << 24, 200], [2], [("S", 1)], [1])
+    sh = v.Sharding(*args)
+    n = v.vesrng_local_shape(sh)[1]
+    say("pieces: aligned rows of 100, %d elements" % n)
+    wins = windows(n, 100)
+    y = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    v.vesrng_normal(sh, v.BF16, 0.0, 1.0, seed, offset, y)
+    torch.cuda.synchronize()
+    got = np.zeros(n, dtype=np.uint16)              # untouched pages cost nothing
+    for b, e in wins:
+        got[b:e] = y[b:e].view(torch.int16).cpu().numpy().view(np.uint16)
+    for b, e in wins:
+        check_normal(got, args, "bf16", 0.0, 1.0, seed, offset, "pieces normal bf16 [%d, %d)" % (b, e), i_begin=b, i_end=e)
+    del got
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    x = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    x.normal_(generator=gen)
+    r = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    r.normal_(generator=gen)
+    mask = torch.empty(n, dtype=torch.uint8, device=DEV)
+    v.vesrng_dropout(sh, v.BF16, 0.25, seed, offset, x, y, mask)
+    torch.cuda.synchronize()
+    xh = np.zeros(n, dtype=np.uint16)
+    for b, e in wins:
+        xh[b:e] = x[b:e].view(torch.int16).cpu().numpy().view(np.uint16)
+    for b, e in wins:
+        yo, mo = oracle.dropout(args, oracle.BF16, 0.25, seed, offset, xh, i_begin=b, i_end=e)
+        assert np.array_equal(mask[b:e].cpu().numpy(), mo.reshape(-1)[b:e]), (b, e)
+        assert_float_bits_equal(y[b:e].view(torch.int16).cpu().numpy().view(np.uint16), yo.reshape(-1)[b:e],
+                                "pieces dropout bf16 [%d, %d)" % (b, e))
+    del xh
+    # Dropout + residual (the residual pointer moves with the pieces too): the lower half of the rows is also a shard
+    # of its own (rows cut in two as well) that fits 32-bit indices and holds the piece boundary; same values expected.
+    v.vesrng_dropout_add(sh, v.BF16, 0.25, seed, offset, x, r, y, mask)
+    half = (1 << 23) * 100
+    sub = v.Sharding([1 << 24, 200], [2, 2], [("S", 1), ("S", 0)], [1, 1])
+    assert v.vesrng_local_shape(sub)[1] == half and half < ((1 << 30) // 100 // 32 * 32) * 100 < n
+    y2 = torch.empty(half, dtype=torch.bfloat16, device=DEV)
+    m2 = torch.empty(half, dtype=torch.uint8, device=DEV)
+    v.vesrng_dropout_add(sub, v.BF16, 0.25, seed, offset, x[half:], r[half:], y2, m2)
+    torch.cuda.synchronize()
+    assert torch.equal(m2, mask[half:]) and torch.equal(y2.view(torch.int16), y[half:].view(torch.int16))
+    del x, r, y, mask, y2, m2
+
+    # Rows of 2^26 elements: fewer than 32 fit a piece, so the 64-bit kernels serve the shard as a whole.
+    args = ([16, 1 << 13, 1 << 14], [2], [("S", 1)], [1])
+    sh = v.Sharding(*args)
+    n = v.vesrng_local_shape(sh)[1]
+    assert n == 1 << 30
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    v.vesrng_uniform(sh, v.F32, 0.0, 1.0, seed, offset, out)
+    torch.cuda.synchronize()
+    for b, e in ((0, width), (n // 2 - width, n // 2 + width), (n - width, n)):
+        want = oracle.uniform(args, oracle.F32, 0.0, 1.0, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(out[b:e].cpu().numpy(), want), (b, e)
+    del out
+
+
 # ------------------------------------------------------------- binary16 -------
 F16_CASES = [([64, 4096], [4], [("S", 0)], [3]),                                 # aligned
              ([6, 64, 512], [2, 2], [("S", 1), ("S", 0)], [1, 1]),               # aligned, several runs of whole wavefronts

@@ -363,3 +363,30 @@ def test_divisions_by_launch_constants_against_exact_integers(host_check):
         assert [int(x) for x in wide.split()] == [x // d for x in ns], d
         if d <= 2 ** 31:
             assert [int(x) for x in narrow.split()] == [x // d for x in ns if x < 2 ** 31], d
+
+
+def test_shards_that_need_64_bit_indices_are_cut_into_pieces(host_check):
+    """A shard of 2^30 elements and more is served by the 32-bit kernels piece by piece when its outermost axis of
+    runs can be cut into groups of 32 or more indices that fit: the pieces cover the axis, fit, and start on
+    128-byte lines; a shard that cannot be cut (one run; rows too long) keeps the 64-bit kernels."""
+    cases = [([2 ** 17, 2 ** 15], [2], [("S", 1)], [1], 4, True, 2 ** 14, 2 ** 17, 2 ** 15),      # rows of 16384 elements
+             ([2 ** 25, 100], [2], [("S", 1)], [1], 4, True, 50, 2 ** 25, 100),                   # rows of 50
+             ([2 ** 20, 4099], [2], [("S", 1)], [1], 4, True, 2049, 2 ** 20, 4099),               # ragged rows
+             ([16, 2 ** 12, 2 ** 15], [2], [("S", 2)], [0], 8, True, 2 ** 14, 2 ** 16, 2 ** 15),  # two axes that merge into one
+             ([16, 2 ** 13, 2 ** 14], [2], [("S", 1)], [1], 8, True, 2 ** 26, 16, 2 ** 27),       # runs of 2^26: 15 rows per piece
+             ([64, 2 ** 26], [2], [("S", 1)], [1], 4, True, 2 ** 25, 64, 2 ** 26),                # rows of 2^25: 31 per piece
+             ([2 ** 32], [2], [("S", 0)], [1], 4, True, None, None, None),                        # a single run
+             ([2 ** 14, 2 ** 15], [2], [("S", 1)], [1], 4, False, None, None, None)]              # fits 32 bits as a whole
+    for shape, mesh, pls, coord, unit_elems, wide, per_index, extent, stride in cases:
+        out = host_check(["P %s 0 %d" % (sharding_words(shape, mesh, pls, coord), unit_elems)])[0].split()
+        assert out[0] == "P" and int(out[1]) == int(wide), shape
+        cut, rows, got_per, got_extent, got_stride, fit = (int(x) for x in out[2:8])
+        if per_index is None:
+            assert (not wide) or cut == 0, shape
+            continue
+        assert (got_per, got_extent, got_stride) == (per_index, extent, stride), shape
+        want_cut = (2 ** 30 - 1) // per_index >= 32 and extent >= 1
+        assert cut == int(want_cut), shape
+        if cut:
+            assert rows % 32 == 0 and rows >= 32 and rows * per_index < 2 ** 30 and fit == 1, shape
+            assert rows + 32 > (2 ** 30 - 1) // per_index      # the largest such group
