@@ -423,7 +423,7 @@ def design_choices(v, B, W, torch, once=False):
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap", "widekernels")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -528,6 +528,23 @@ def design_choices(v, B, W, torch, once=False):
               [("library (kept)", drop(v), 5 * nr), ("general form of the tile map", drop(variants["longmap"]), 5 * nr),
                ("no staging", drop(variants["ragged"]), 5 * nr)])
         del xr, orr, mr
+    # Shards of 2^30 elements and more: piece by piece through the 32-bit kernels against the 64-bit kernels.
+    del o
+    wide_out = torch.empty(1 << 31, dtype=torch.float32, device="cuda")
+    for shape, what in (([1 << 17, 1 << 15], "aligned runs of 16384 elements, 2^31 elements"),
+                        ([1 << 24, 200], "aligned runs of 100 elements, 1.68e9 elements"),
+                        ([1 << 19, 4099], "ragged runs of 2049 elements, 1.07e9 elements")):
+        shw = v.Sharding(shape, [2], [("S", 1)], [1])
+        nw = v.vesrng_local_shape(shw)[1]
+        wf = wide_out[:nw]
+        wb = wide_out.view(torch.bfloat16)[:nw]
+        entry("fp32 uniform fill, " + what, "piece by piece through the 32-bit kernels",
+              [("library (kept)", lambda: v.vesrng_uniform(shw, v.F32, 0.0, 1.0, 1, 0, wf), 4 * nw),
+               ("64-bit index kernels", lambda: variants["widekernels"].vesrng_uniform(shw, v.F32, 0.0, 1.0, 1, 0, wf), 4 * nw)])
+        entry("bf16 normal fill, " + what, "piece by piece through the 32-bit kernels",
+              [("library (kept)", lambda: v.vesrng_normal(shw, v.BF16, 0.0, 1.0, 1, 0, wb), 2 * nw),
+               ("64-bit index kernels", lambda: variants["widekernels"].vesrng_normal(shw, v.BF16, 0.0, 1.0, 1, 0, wb), 2 * nw)])
+    del wide_out
     return res
 
 
