@@ -423,7 +423,7 @@ def design_choices(v, B, W, torch, once=False):
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap", "widekernels")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap", "widekernels", "loopaxes")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -544,7 +544,23 @@ def design_choices(v, B, W, torch, once=False):
         entry("bf16 normal fill, " + what, "piece by piece through the 32-bit kernels",
               [("library (kept)", lambda: v.vesrng_normal(shw, v.BF16, 0.0, 1.0, 1, 0, wb), 2 * nw),
                ("64-bit index kernels", lambda: variants["widekernels"].vesrng_normal(shw, v.BF16, 0.0, 1.0, 1, 0, wb), 2 * nw)])
-    del wide_out
+    # Double-sharded tensors: two and three axes of runs (Table 5's grid), run arithmetic written out against the loop.
+    xa = torch.randn(1 << 27, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    ma = torch.empty(1 << 27, dtype=torch.uint8, device="cuda")
+    for shape, mesh, pls, what in (([256, 256, 8192], [2, 2], [("S", 1), ("S", 2)], "two axes of runs of 4096 elements"),
+                                   ([16, 32, 128, 8192], [2, 2, 2], [("S", 1), ("S", 2), ("S", 3)], "three axes of runs of 4096 elements"),
+                                   ([64, 128, 512, 200], [2, 2, 2], [("S", 1), ("S", 2), ("S", 3)], "three axes of runs of 100 elements")):
+        sha = v.Sharding(shape, mesh, pls, [1] * len(mesh))
+        na = v.vesrng_local_shape(sha)[1]
+        af = wide_out[:na]
+        ab = wide_out.view(torch.bfloat16)[:na]
+        entry("fp32 uniform fill, %s, %d elements" % (what, na), "run arithmetic written out for two and three axes",
+              [("library (kept)", lambda: v.vesrng_uniform(sha, v.F32, 0.0, 1.0, 1, 0, af), 4 * na),
+               ("loop over the axes", lambda: variants["loopaxes"].vesrng_uniform(sha, v.F32, 0.0, 1.0, 1, 0, af), 4 * na)])
+        entry("bf16 dropout, %s, %d elements" % (what, na), "run arithmetic written out for two and three axes",
+              [("library (kept)", lambda: v.vesrng_dropout(sha, v.BF16, 0.1, 1, 0, xa[:na], ab, ma[:na]), 5 * na),
+               ("loop over the axes", lambda: variants["loopaxes"].vesrng_dropout(sha, v.BF16, 0.1, 1, 0, xa[:na], ab, ma[:na]), 5 * na)])
+    del wide_out, xa, ma
     return res
 
 

@@ -55,6 +55,9 @@ TARGETS = {
     # Shards of 2^30 elements and more through the 64-bit index kernels as a whole instead of piece by piece.
     "variant_widekernels": {"lib": "libvesrng_variant_widekernels.so", "sources": PRODUCT_SOURCES,
                             "defines": ["VESRNG_VARIANT_TAG=widekernels", "VESRNG_WIDE_SHARDS_IN_PIECES=0"]},
+    # Two and three axes of runs through the loop over any number of axes instead of the written-out forms.
+    "variant_loopaxes": {"lib": "libvesrng_variant_loopaxes.so", "sources": PRODUCT_SOURCES,
+                         "defines": ["VESRNG_VARIANT_TAG=loopaxes", "VESRNG_EXACT_RUN_AXES=1"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

@@ -11,6 +11,19 @@
 
 using namespace vesrng;
 
+namespace {
+template <typename IT>
+uint64_t position_of_run(const vesrng::PlanT<IT>& plan, IT run) {
+  switch (plan.n_outer) {
+    case 0: return vesrng::run_position<0>(plan, run);
+    case 1: return vesrng::run_position<1>(plan, run);
+    case 2: return vesrng::run_position<2>(plan, run);
+    case 3: return vesrng::run_position<3>(plan, run);
+    default: return vesrng::run_position<vesrng::kAnyAxes>(plan, run);
+  }
+}
+}  // namespace
+
 extern "C" {
 
 vesrng_status vesrng_local_shape(const vesrng_sharding* s, int64_t* local_shape, int64_t* local_numel) {
@@ -60,7 +73,8 @@ vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int
     return VESRNG_OK;
   }
   const RunShape rs = run_shape(g);
-  // Same plan types and decode routine as the kernels, compiled for the host.
+  // Same plan types and decode routines as the kernels, compiled for the host, chosen as the kernels' launcher
+  // chooses them (the forms written out for one and two axes of runs, the loop for more).
   const bool narrow = fits_32bit(rs, rs.run_len);
   const PlanT<uint32_t> p32 = narrow ? make_plan<uint32_t>(g, rs, 0, rs.run_len) : PlanT<uint32_t>{};
   const PlanT<uint64_t> p64 = make_plan<uint64_t>(g, rs, 0, rs.run_len);
@@ -70,11 +84,11 @@ vesrng_status vesrng_global_index(const vesrng_sharding* s, int64_t n, const int
     if (narrow) {
       const uint32_t w = static_cast<uint32_t>(i);
       const uint32_t run = p32.units_div.div(w);
-      global_index[k] = p32.pos0 + run_offset(p32, run) + (w - run * p32.units_per_run);
+      global_index[k] = position_of_run(p32, run) + (w - run * p32.units_per_run);
     } else {
       const uint64_t w = static_cast<uint64_t>(i);
       const uint64_t run = p64.units_div.div(w);
-      global_index[k] = p64.pos0 + run_offset(p64, run) + (w - run * p64.units_per_run);
+      global_index[k] = position_of_run(p64, run) + (w - run * p64.units_per_run);
     }
   }
   return VESRNG_OK;

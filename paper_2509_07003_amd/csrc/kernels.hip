@@ -76,6 +76,11 @@
 #ifndef VESRNG_WIDE_SHARDS_IN_PIECES
 #define VESRNG_WIDE_SHARDS_IN_PIECES 1
 #endif
+// 3 (always, in the library): shards with two and three axes of runs take kernels whose run arithmetic is written
+// out for that number of axes.  1 only in the measurement variant that serves them with the loop over any number.
+#ifndef VESRNG_EXACT_RUN_AXES
+#define VESRNG_EXACT_RUN_AXES 3
+#endif
 #ifndef VESRNG_TILE_SAME_PHASE
 #define VESRNG_TILE_SAME_PHASE 1
 #endif
@@ -966,8 +971,17 @@ hipError_t launch_typed(Flavour flavour, const Geometry& g, const RunShape& rs, 
   switch (plan.n_outer) {
     case 0: return launch_nout<OP, DT, IT, 0>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
     case 1: return launch_nout<OP, DT, IT, 1>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
-    default: return launch_nout<OP, DT, IT, 2>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
+    case 2:
+      if constexpr (VESRNG_EXACT_RUN_AXES >= 2)
+        return launch_nout<OP, DT, IT, 2>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
+      break;
+    case 3:
+      if constexpr (VESRNG_EXACT_RUN_AXES >= 3)
+        return launch_nout<OP, DT, IT, 3>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
+      break;
+    default: break;
   }
+  return launch_nout<OP, DT, IT, kAnyAxes>(flavour, plan, tile_units, n, prm, x, out, mask, stream);
 }
 
 template <int OP, int DT>

@@ -112,15 +112,32 @@ struct SignedOf<uint64_t> {
   using type = int64_t;
 };
 
-// Stream position of the first element of run `run`.  NOUT is the number of
-// run-enumerating axes known at compile time (0, 1) or 2 for "any number": the common
-// shards (a contiguous slice; one strided axis of runs) need no loop and no argument
-// loads that depend on a loop counter.
+// Stream position of the first element of run `run`.  NOUT is the number of run-enumerating axes known at
+// compile time (0 to 3) or 4 for "any number": the common shards (a contiguous slice; one strided axis of
+// runs; two or three, as double sharding of a tensor of three to five dimensions gives - Table 5's grid) need
+// no loop and no argument loads that depend on a loop counter, so their constants arrive with the rest of the
+// kernel's arguments.
+constexpr int kAnyAxes = 4;
 template <int NOUT, typename IT>
 VESRNG_HD uint64_t run_position(const PlanT<IT>& plan, IT run) {
-  if constexpr (NOUT == 0) return plan.pos0;
-  else if constexpr (NOUT == 1) return plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
-  else return plan.pos0 + run_offset(plan, run);
+  if constexpr (NOUT == 0) {
+    return plan.pos0;
+  } else if constexpr (NOUT == 1) {
+    return plan.pos0 + static_cast<uint64_t>(run) * plan.outer_stride[0];
+  } else if constexpr (NOUT == 2) {
+    const IT c1 = plan.outer_div[0].div(run);
+    const IT c0 = run - c1 * plan.outer_extent[0];
+    return plan.pos0 + static_cast<uint64_t>(c0) * plan.outer_stride[0] + static_cast<uint64_t>(c1) * plan.outer_stride[1];
+  } else if constexpr (NOUT == 3) {
+    const IT q0 = plan.outer_div[0].div(run);
+    const IT c0 = run - q0 * plan.outer_extent[0];
+    const IT c2 = plan.outer_div[1].div(q0);
+    const IT c1 = q0 - c2 * plan.outer_extent[1];
+    return plan.pos0 + static_cast<uint64_t>(c0) * plan.outer_stride[0] + static_cast<uint64_t>(c1) * plan.outer_stride[1] +
+           static_cast<uint64_t>(c2) * plan.outer_stride[2];
+  } else {
+    return plan.pos0 + run_offset(plan, run);
+  }
 }
 
 // Work unit w -> (run, unit inside the run, stream position of the run).

@@ -174,7 +174,9 @@ void tiles_typed(const Geometry& g, const RunShape& rs, uint64_t offset, const L
     switch (plan.n_outer) {
       case 0: emulate_tile<IT, 0>(plan, ta, unit_elems, t); break;
       case 1: emulate_tile<IT, 1>(plan, ta, unit_elems, t); break;
-      default: emulate_tile<IT, 2>(plan, ta, unit_elems, t); break;
+      case 2: emulate_tile<IT, 2>(plan, ta, unit_elems, t); break;
+      case 3: emulate_tile<IT, 3>(plan, ta, unit_elems, t); break;
+      default: emulate_tile<IT, kAnyAxes>(plan, ta, unit_elems, t); break;
     }
   }
 }
