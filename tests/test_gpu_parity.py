@@ -717,6 +717,58 @@ def test_random_descriptions_all_kernel_flavours():
         done += 1
 
 
+def test_random_mid_sized_descriptions():
+    """Seeded random tensors of two to five dimensions with 1 M to 12 M local elements on random meshes (Shard and
+    InterleavedShard, some with padded global strides): sizes at which the staging windows of the operators, the
+    large tile, and the kernels written out for one, two and three axes of runs are all in play.  Raw draws, the bf16
+    uniform fill, the fp32 normal fill and fused bf16 dropout against the threaded oracle."""
+    rng = np.random.default_rng(31415)
+    done = 0
+    while done < 14:
+        nd = int(rng.integers(2, 6))
+        target = float(rng.uniform(2e6, 4e7))
+        cuts = np.sort(rng.uniform(0, 1, size=nd - 1))
+        parts = np.diff(np.concatenate([[0.0], cuts, [1.0]]))
+        shape = [max(2, int(round(target ** p))) for p in parts]
+        if rng.random() < 0.6:
+            shape[-1] = max(shape[-1], int(rng.integers(64, 3000)))      # an innermost dimension long enough to tile
+        md = int(rng.integers(1, 4))
+        mesh = [int(x) for x in rng.integers(2, 4, size=md)]
+        pls = []
+        for _ in range(md):
+            d = int(rng.integers(0, nd))
+            pls.append(("S", d) if rng.random() < 0.8 else ("IS", d, int(rng.integers(2, 4))))
+        coord = [int(rng.integers(0, p)) for p in mesh]
+        stride = None
+        if rng.random() < 0.25:
+            stride, acc = [0] * nd, 1
+            for d in range(nd - 1, -1, -1):
+                stride[d] = acc
+                acc *= shape[d] + int(rng.integers(0, 4))
+        try:
+            n = oracle.local_shape(shape, mesh, pls, coord)[1]
+        except oracle.OracleError:
+            continue
+        if n < 1_000_000 or n > 12_000_000 or int(np.prod(shape)) > 150_000_000:
+            continue
+        seed, offset = int(rng.integers(0, 2 ** 63)), 4 * int(rng.integers(0, 2 ** 40))
+        args = (shape, mesh, pls, coord, stride)
+        what = "%s (%d local elements)" % (args, n)
+        say("random mid-sized " + what)
+        got = gpu_fill("raw", None, args, seed, offset)
+        assert np.array_equal(got, oracle.raw_u32(args, seed, offset, threads=THREADS)), what
+        got = gpu_fill("uniform", "bf16", args, seed, offset, low=-2.0, high=2.0)
+        assert np.array_equal(got, oracle.uniform(args, oracle.BF16, -2.0, 2.0, seed, offset, threads=THREADS)), what
+        got = gpu_fill("normal", "f32", args, seed, offset, mean=0.25, std=1.5)
+        check_normal(got, args, "f32", 0.25, 1.5, seed, offset, "normal f32 " + what)
+        x = W.bf16_bits_from_f32(W.adversarial_f32(n, seed=done))
+        yo, mo = oracle.dropout(args, oracle.BF16, 0.2, seed, offset, x, threads=THREADS)
+        y, mk = gpu_dropout("bf16", args, 0.2, seed, offset, x)
+        assert np.array_equal(mk, mo), what
+        assert_float_bits_equal(y, yo, "dropout bf16 " + what)
+        done += 1
+
+
 def test_ceiling_probes_do_what_they_say():
     """The measurement aids (their own library): store patterns in every form, copy, dropout traffic
     pattern, generator-only and issue-rate loops, the clock probe and the device properties the
