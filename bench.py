@@ -423,7 +423,7 @@ def design_choices(v, B, W, torch, once=False):
            ("two v_xor_b32", lambda: probe(B.PROBE_PHILOX_TWO_XOR, blocks, None, a), blocks * 16)])
     del a, b, m
 
-    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap", "widekernels", "loopaxes")}
+    variants = {k: B.Variant(k) for k in ("nopin", "ntstore", "twoxor", "lanerun", "ragged", "realign", "smalltile", "bigtile", "wavetile", "longmap", "nocap", "widekernels", "loopaxes", "pairint")}
     # Aligned kernels: C5's dropout shard, a 2^28-element fp32 uniform fill, C3 x64 (bf16 normal).
     w = W.C5
     sh5 = v.Sharding(*w.sharding_args(w.bench_coord))
@@ -560,7 +560,17 @@ def design_choices(v, B, W, torch, once=False):
         entry("bf16 dropout, %s, %d elements" % (what, na), "run arithmetic written out for two and three axes",
               [("library (kept)", lambda: v.vesrng_dropout(sha, v.BF16, 0.1, 1, 0, xa[:na], ab, ma[:na]), 5 * na),
                ("loop over the axes", lambda: variants["loopaxes"].vesrng_dropout(sha, v.BF16, 0.1, 1, 0, xa[:na], ab, ma[:na]), 5 * na)])
-    del wide_out, xa, ma
+    # randint (8 bytes per element): two threads per generator block against one thread with two stores.
+    oi64 = wide_out.view(torch.int64)
+    for shape, mesh, pls, what in (([1 << 28], [1], [("R",)], "contiguous shard of 2^28 elements"),
+                                   ([1 << 15, 8192], [2], [("S", 1)], "runs of 4096 elements, 2^27 elements")):
+        shi = v.Sharding(shape, mesh, pls, [p - 1 for p in mesh])
+        ni = v.vesrng_local_shape(shi)[1]
+        entry("randint fill, " + what, "two threads per generator block, one 16-byte store each",
+              [("library (kept)", lambda: v.vesrng_randint(shi, 0, 1000, 1, 0, oi64[:ni]), 8 * ni),
+               ("one thread per block, halves traded across lanes, two stores",
+                lambda: variants["pairint"].vesrng_randint(shi, 0, 1000, 1, 0, oi64[:ni]), 8 * ni)])
+    del wide_out, xa, ma, oi64
     return res
 
 

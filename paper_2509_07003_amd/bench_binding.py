@@ -93,6 +93,9 @@ class Variant:
         _check(self._lib.vesrng_dropout(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(y), _dev(mask),
                                         _stream(stream, x, y, mask)))
 
+    def vesrng_randint(self, sharding, low, high, seed, offset, out, stream=None):
+        _check(self._lib.vesrng_randint(C.byref(sharding.c), low, high, seed, offset, _dev(out), _stream(stream, out)))
+
     def vesrng_dropout_add(self, sharding, dtype, p, seed, offset, x, residual, y, mask=None, stream=None):
         _check(self._lib.vesrng_dropout_add(C.byref(sharding.c), dtype, p, seed, offset, _dev(x), _dev(residual),
                                             _dev(y), _dev(mask), _stream(stream, x, residual, y, mask)))

@@ -58,6 +58,9 @@ TARGETS = {
     # Two and three axes of runs through the loop over any number of axes instead of the written-out forms.
     "variant_loopaxes": {"lib": "libvesrng_variant_loopaxes.so", "sources": PRODUCT_SOURCES,
                          "defines": ["VESRNG_VARIANT_TAG=loopaxes", "VESRNG_EXACT_RUN_AXES=1"]},
+    # Aligned randint with one thread per generator block, halves traded between neighbouring lanes, two stores per thread.
+    "variant_pairint": {"lib": "libvesrng_variant_pairint.so", "sources": PRODUCT_SOURCES,
+                        "defines": ["VESRNG_VARIANT_TAG=pairint", "VESRNG_RANDINT_HALF_BLOCKS=0"]},
     # Ragged shards: never staged through LDS, whole blocks stored element-aligned / realigned across lanes.
     "variant_ragged": {"lib": "libvesrng_variant_ragged.so", "sources": PRODUCT_SOURCES,
                        "defines": ["VESRNG_VARIANT_TAG=ragged", "VESRNG_TILING=0"]},

@@ -81,6 +81,11 @@
 #ifndef VESRNG_EXACT_RUN_AXES
 #define VESRNG_EXACT_RUN_AXES 3
 #endif
+// 1 (always, in the library): the aligned randint fill runs two threads per generator block, each storing one half.
+// 0 only in the measurement variant that runs one thread per block and trades halves between neighbouring lanes.
+#ifndef VESRNG_RANDINT_HALF_BLOCKS
+#define VESRNG_RANDINT_HALF_BLOCKS 1
+#endif
 #ifndef VESRNG_TILE_SAME_PHASE
 #define VESRNG_TILE_SAME_PHASE 1
 #endif
@@ -400,11 +405,31 @@ aligned_kernel(const PlanT<IT> plan, const OpParams prm, const void* xin, void* 
 #if VESRNG_PIN_ARGUMENT_FETCH
   asm volatile("" ::"s"(out), "s"(mask));
 #endif
-  // randint writes 32 bytes per generator block.  Lane by lane that would be two stores of 16
-  // bytes at a 32-byte stride, which run at a third of the contiguous rate.  Instead the lane
-  // pair (2k, 2k+1) of a wave computes blocks k and 32 + k of the wave's 64 and the two trade
-  // halves, so that either store instruction writes 1 KiB without gaps.
+  // randint writes 32 bytes per generator block.  Lane by lane that would be two stores of 16 bytes at a 32-byte
+  // stride, which run at a third of the contiguous rate (2.35 TB/s).  The library runs TWO threads per block: thread
+  // t computes block t / 2 - the generator is cheap next to 16 bytes of HBM traffic - and stores the half t % 2 (two
+  // integers, 16 bytes): one store instruction per thread, a wave's kilobyte contiguous: 7.3 TB/s on a contiguous
+  // shard, 6.85 with runs.  The form it replaced (measurement variant only) keeps one thread per block: the lane pair
+  // (2k, 2k+1) of a wave computes blocks k and 32 + k of the wave's 64 and the two trade halves across lanes, so that
+  // either of a thread's TWO store instructions writes 1 KiB without gaps: 5.9 TB/s, the rate of every kernel here
+  // that issues two 16-byte stores per thread.
   const uint32_t lane = threadIdx.x & 63u;
+  constexpr bool kHalf = (OP == kOpRandint) && (VESRNG_RANDINT_HALF_BLOCKS != 0) && !WAVE;
+  if constexpr (kHalf) {
+    const uint64_t t64 = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const bool on = (t64 >> 1) < plan.total_units;
+    const uint64_t w = on ? (t64 >> 1) : 0;
+    IT run, unit;
+    uint64_t run_pos;
+    locate<NOUT>(plan, static_cast<IT>(w), run, unit, run_pos);
+    uint32_t d[4];
+    philox_block((run_pos + static_cast<uint64_t>(unit) * V) >> 2, prm.key0, prm.key1, d);
+    asm volatile("" : "+v"(d[0]), "+v"(d[1]), "+v"(d[2]), "+v"(d[3]));
+    if (!on) return;
+    const bool hi = (t64 & 1u) != 0u;
+    store_randint_pair(hi ? d[2] : d[0], hi ? d[3] : d[1], prm, out, t64);
+    return;
+  }
   const uint32_t slot = (OP == kOpRandint) ? (lane >> 1) + ((lane & 1u) << 5) : lane;  // the wave's unit this lane takes
   uint64_t wave_base, w64, block0;
   bool live;
@@ -930,6 +955,8 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
   uint64_t blocks;
   if (flavour == kTiled || flavour == kTiledBig)
     blocks = (local_numel + tile_units * V - 1) / (tile_units * V);
+  else if (OP == kOpRandint && VESRNG_RANDINT_HALF_BLOCKS != 0 && flavour == kAligned)
+    blocks = (2 * plan.total_units + kThreads - 1) / kThreads;
   else
     blocks = (plan.total_units + kThreads - 1) / kThreads;
   if (blocks == 0) return hipSuccess;
@@ -940,7 +967,7 @@ hipError_t launch_nout(Flavour flavour, const PlanT<IT>& plan, uint64_t tile_uni
       size_t cap = 0;
       if constexpr (kIsDropout<OP> && VESRNG_CAP_MASKED_DROPOUT_WAVES != 0)
         if (mask != nullptr && plan.total_units >= kWaveCapMinUnits) cap = kWaveCapLdsBytes;
-      if constexpr (NOUT != 0 && VESRNG_WAVE_UNIFORM_RUNS != 0)
+      if constexpr (NOUT != 0 && VESRNG_WAVE_UNIFORM_RUNS != 0 && !(OP == kOpRandint && VESRNG_RANDINT_HALF_BLOCKS != 0))
         if (plan.wave_runs)
           return enqueue_with_lds(aligned_kernel<OP, DT, IT, NOUT, true>, grid, block, cap, stream, plan, prm, x, out,
                                   mask);
