@@ -1122,6 +1122,15 @@ def test_shards_beyond_2_to_30_elements_served_piece_by_piece():
     for b, e in windows(nw, 37):
         want = oracle.randint(args_w, -7, 1 << 31, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
         assert np.array_equal(outi[b:e].cpu().numpy(), want), (b, e)
+    args_a = ([1 << 25, 72], [2], [("S", 1)], [1])          # rows of 36 from column 36: whole blocks, the aligned kernel
+    sh_a = v.Sharding(*args_a)
+    na = v.vesrng_local_shape(sh_a)[1]
+    assert (1 << 30) < na <= nw
+    v.vesrng_randint(sh_a, 0, 1000, seed, offset, outi[:na])
+    torch.cuda.synchronize()
+    for b, e in windows(na, 36):
+        want = oracle.randint(args_a, 0, 1000, seed, offset, i_begin=b, i_end=e).reshape(-1)[b:e]
+        assert np.array_equal(outi[b:e].cpu().numpy(), want), (b, e)
     del outi
 
     # Rows of 100 aligned elements: bf16 normal fill and fused dropout + residual.
